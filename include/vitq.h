@@ -1,0 +1,178 @@
+/*
+ * vitq -- integerized ViT block matmuls (operand reordering) for AMD MI355X (gfx950).
+ *
+ * C ABI of libvitq.so.  Every matrix operation of a ViT block (QKV / projection / MLP
+ * linears, Q.K^T, P.V) runs directly on packed b-bit integer operands with exact int32
+ * accumulation; dequantization is moved AFTER the matmul and fused, with bias, activation and
+ * requantization, into the kernel epilogue (paper: Sec. III-A, Eq. 2; Sec. IV-B, Eq. 3-4).
+ *
+ * General conventions
+ *   - All data pointers are DEVICE pointers unless a parameter says "host".  Every buffer
+ *     (inputs, outputs, workspace) is owned by the caller; the library allocates and frees
+ *     nothing and keeps no state.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue
+ *     work on it and return without synchronizing.
+ *   - Errors are reported by return code only.  All argument checks run on the host before
+ *     anything is launched; a failed check leaves every output untouched.
+ *   - Nullable outputs select what the epilogue writes.
+ *
+ * Quantizer (paper: Sec. IV-B lists the 3-bit comparator references -3.5..2.5 x step;
+ * Sec. IV-C gives the general (k - 1/2) x step): level = clamp(round(x / step), qmin, qmax)
+ * with qmin = -2^(b-1), qmax = 2^(b-1)-1; x/step is an IEEE fp32 division and exact halves
+ * round to the even level.  The attention matrix P is unsigned: levels 0..2^b-1, step
+ * 1/(2^b-1).
+ */
+#ifndef VITQ_H
+#define VITQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum vq_status {
+    VQ_OK = 0,
+    VQ_ERR_NULL = 1,        /* a required pointer is NULL                                  */
+    VQ_ERR_SHAPE = 2,       /* dimensions non-positive, mismatching or too large           */
+    VQ_ERR_BITS = 3,        /* bits / storage_bits / signedness not valid for this operand */
+    VQ_ERR_STRIDE = 4,      /* row_stride too small, or stride / pointer not 16-B aligned  */
+    VQ_ERR_STEP = 5,        /* a host-visible step size is not a positive finite number    */
+    VQ_ERR_UNSUPPORTED = 6, /* valid request this build has no kernel for                  */
+    VQ_ERR_WORKSPACE = 7,   /* workspace NULL or too small                                 */
+    VQ_ERR_HIP = 8          /* the HIP runtime refused a launch                            */
+} vq_status;
+
+/*
+ * A packed quantized matrix in device memory (the interchange format).
+ * Element (r, c) occupies `storage_bits` bits at byte r*row_stride + (c*storage_bits)/8,
+ * bit offset (c*storage_bits)%8 -- element 0 sits in the least-significant field; signed
+ * levels are two's complement.  storage_bits is 2, 4 or 8; `bits` (2..8, <= storage_bits) is
+ * the level range (3-bit levels live in 4-bit fields).  Rows are packed along `cols`, which is
+ * the contraction dimension whenever the matrix is a matmul operand.
+ * row_stride is in bytes and a multiple of 16; `data` is 16-byte aligned.  In an INPUT, the
+ * bytes from ceil(cols*storage_bits/8) up to the next multiple of 16 must be zero.  In an
+ * OUTPUT, the library writes bytes [0, that multiple of 16) of every row (zeros in the pad)
+ * and touches nothing beyond.
+ */
+typedef struct vq_qmat {
+    void *data;
+    int32_t bits;
+    int32_t storage_bits;
+    int32_t is_unsigned; /* 1 only for the attention matrix P */
+    int32_t reserved;
+    int64_t rows;
+    int64_t cols;
+    int64_t row_stride;
+} vq_qmat;
+
+const char *vq_status_string(vq_status s);
+
+/*
+ * Per-row (per-output-channel) weight steps: step_out[r] = max_c |w[r][c]| / qmax(bits) in
+ * fp32, or 1 for an all-zero row.  (The benchmark configurations' rule; the paper takes its
+ * steps from a trained low-bit checkpoint, Sec. V-A.)
+ * w: device fp32 [rows x cols], leading dimension ld (elements).  step_out: device [rows].
+ */
+vq_status vq_weight_steps(const float *w, int64_t rows, int64_t cols, int64_t ld, int32_t bits,
+                          float *step_out, void *stream);
+
+/*
+ * Uniform b-bit quantizer (see the top of this file), writing the packed format.
+ * x: device fp32 [rows x cols], leading dimension ld.  `step` (host scalar) is the per-tensor
+ * step; if step_per_row (device, [rows]) is non-NULL it overrides `step` row by row.
+ * out: describes the destination (data, bits, storage_bits, rows, cols, row_stride are read;
+ * is_unsigned must be 0).  Errors: NULL, SHAPE (rows/cols mismatch), BITS, STRIDE, STEP.
+ */
+vq_status vq_quantize(const float *x, int64_t rows, int64_t cols, int64_t ld, float step,
+                      const float *step_per_row, const vq_qmat *out, void *stream);
+
+/*
+ * Reordered (integerized) linear layer, Eq. 2 with a scalar activation step:
+ *     acc[m][c] = sum_k xq[m][k] * wq[c][k]                    exact, int32
+ *     y[m][c]   = fma((float)acc, s_x * s_w[c], bias[c])       post-scaling, fp32
+ *     act == 1:   y = gelu(y)   (tanh form, fixed fp32 operation sequence)
+ *     yq        = quantize(y, s_y) packed with yq_out's bits
+ * xq: [M x K]; wq: [Nout x K]; both packed along K.  s_w: device, [Nout] if s_w_per_channel
+ * else [1].  bias: device [Nout] or NULL.  acc_out: device int32 [M x Nout] or NULL.
+ * y_out: device fp32 [M x Nout] or NULL.  yq_out: destination descriptor or NULL
+ * (rows = M, cols = Nout); s_y is its per-tensor step (host scalar).
+ * Supported (weight storage, activation storage) pairs: (4,4), (2,4), (8,8).
+ * Errors: NULL, SHAPE (K mismatch, K > 65536, sizes overflowing int32 indexing), BITS,
+ * STRIDE, STEP (s_x or s_y not positive finite), UNSUPPORTED.
+ */
+vq_status vq_linear(const vq_qmat *xq, float s_x, const vq_qmat *wq, const float *s_w,
+                    int32_t s_w_per_channel, const float *bias, int32_t act, int32_t *acc_out,
+                    float *y_out, float s_y, const vq_qmat *yq_out, void *stream);
+
+/*
+ * Q.K^T per (image, head) followed by the quantized softmax (Eq. 3-4 and the row-sum-scaled
+ * comparator of Sec. IV-B):
+ *     S[i][j] = sum_d q[i][d] * k[j][d]                        exact, int32
+ *     alpha   = ((s_q*s_k)*scale)*log2(e)                      fp32, in this order
+ *     e_j     = ((1+r) * 2^20) >> -floor(alpha*(S_ij - max_j S_ij)),  r the fractional part
+ *     P[i][j] = #{ k in 1..pmax : 2*pmax*e_j > (2k-1) * sum_j e_j },  pmax = 2^bits - 1
+ * q, k: packed [B*H*N x 64], head-major (row = (b*H + h)*N + token), signed, same bits.
+ * s_acc_out: device int32 [B*H*N x N] or NULL.  p_out: unsigned destination [B*H*N x N] or
+ * NULL.  Limits: head dimension 64, N <= 592.
+ */
+vq_status vq_matmul_qk(const vq_qmat *q, const vq_qmat *k, int32_t B, int32_t H, int32_t N,
+                       float s_q, float s_k, float scale, int32_t *s_acc_out,
+                       const vq_qmat *p_out, void *stream);
+
+/*
+ * P.V per (image, head) with both operand scales absorbed next to the output quantizer
+ * (Sec. IV-B, weighted sum of values):
+ *     O[i][d] = sum_j p[i][j] * v[j][d]                        exact, int32
+ *     o       = (float)O * (s_p * s_v);     oq = quantize(o, s_o)
+ * p: unsigned packed [B*H*N x N]; v: packed [B*H*N x 64] head-major.
+ * o_acc_out: device int32 [B*H*N x 64] or NULL.  o_out: device fp32 [B*N x H*64] (heads
+ * concatenated along the channel axis) or NULL.  oq_out: destination [B*N x H*64] or NULL.
+ */
+vq_status vq_matmul_pv(const vq_qmat *p, const vq_qmat *v, int32_t B, int32_t H, int32_t N,
+                       float s_p, float s_v, int32_t *o_acc_out, float *o_out, float s_o,
+                       const vq_qmat *oq_out, void *stream);
+
+/*
+ * One whole block: X_q -> QKV linear -> Q,K,V requantized with their own steps -> Q.K^T ->
+ * quantized softmax -> P.V -> O_q -> projection [-> X2_q -> fc1 + GELU -> H_q -> fc2] -> Y.
+ * Output channel c of the QKV linear is (q/k/v, head, d) = (c / D, (c % D) / 64, c % 64).
+ * Scores and P never leave the chip.  hidden == 0 selects the attention-only chain.
+ * No residual connection and no LayerNorm are part of the chain.
+ */
+typedef struct vq_block_desc {
+    int32_t D, H, N, hidden;
+    int32_t bits_a;               /* activation levels (signed): X, Q, K, V, O, X2, H      */
+    int32_t bits_p;               /* attention levels (unsigned)                           */
+    int32_t storage_a;            /* storage bits of every activation tensor: 4 or 8       */
+    int32_t reserved;
+    vq_qmat w_qkv, w_proj, w_fc1, w_fc2; /* [3D x D] [D x D] [hidden x D] [D x hidden]     */
+    const float *sw_qkv, *b_qkv;  /* per-channel steps and biases, device                  */
+    const float *sw_proj, *b_proj;
+    const float *sw_fc1, *b_fc1;
+    const float *sw_fc2, *b_fc2;
+    float s_x, s_q, s_k, s_v, s_o, s_x2, s_h, scale; /* per-tensor steps; scale = 1/sqrt(64) */
+    /* Optional copies of the intermediates (device, nullable).  When given, the stage writes
+     * there instead of into the workspace -- same kernels, same code path.                  */
+    void *dump_qkv;   /* packed [3][B*H*N][64*storage_a/8]  (Q, then K, then V; head-major)  */
+    void *dump_o;     /* packed [B*N][D*storage_a/8]                                         */
+    void *dump_x2;    /* packed [B*N][D*storage_a/8]        (hidden > 0 only)                */
+    void *dump_h;     /* packed [B*N][hidden*storage_a/8]   (hidden > 0 only)                */
+} vq_block_desc;
+
+/* Bytes of workspace vq_attention_block needs for batch B (host computation only). */
+vq_status vq_attention_block_workspace(const vq_block_desc *desc, int64_t B, size_t *bytes);
+
+/*
+ * xq: packed [B*N x D] tokens (step desc->s_x).  y_out: device fp32 [B*N x D].
+ * workspace: device, 256-byte aligned, at least the size reported above.
+ */
+vq_status vq_attention_block(const vq_block_desc *desc, const vq_qmat *xq, int64_t B,
+                             float *y_out, void *workspace, size_t workspace_bytes,
+                             void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VITQ_H */

@@ -1,0 +1,401 @@
+// C ABI of libvitq.so: argument validation on the host, then kernel launches.
+// No allocation, no synchronization, no global state.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "../../include/vitq.h"
+#include "attention.h"
+#include "gemm.h"
+#include "quantize.h"
+
+using namespace vitq;
+
+namespace {
+
+bool good_step(float s) { return isfinite(s) && s > 0.0f; }
+
+int64_t row_bytes(const vq_qmat *m) { return (m->cols * m->storage_bits + 7) / 8; }
+int64_t row_bytes16(const vq_qmat *m) { return (row_bytes(m) + 15) / 16 * 16; }
+
+// Structural checks of a packed-matrix descriptor.
+vq_status check_qmat(const vq_qmat *m, int want_unsigned) {
+    if (!m) return VQ_ERR_NULL;
+    if (m->rows < 0 || m->cols <= 0 || m->rows > INT32_MAX || m->cols > INT32_MAX) return VQ_ERR_SHAPE;
+    if (m->storage_bits != 2 && m->storage_bits != 4 && m->storage_bits != 8) return VQ_ERR_BITS;
+    if (m->bits < 2 || m->bits > 8 || m->bits > m->storage_bits) return VQ_ERR_BITS;
+    if ((m->is_unsigned != 0) != (want_unsigned != 0)) return VQ_ERR_BITS;
+    if (m->row_stride <= 0 || m->row_stride % 16 != 0 || m->row_stride < row_bytes(m)) return VQ_ERR_STRIDE;
+    if (m->rows > 0 && !m->data) return VQ_ERR_NULL;
+    if (((uintptr_t)m->data) % 16 != 0) return VQ_ERR_STRIDE;
+    return VQ_OK;
+}
+
+void level_range(int bits, float *qminf, float *qmaxf) {
+    *qminf = -(float)(1 << (bits - 1));
+    *qmaxf = (float)((1 << (bits - 1)) - 1);
+}
+
+bool pair_supported(int wb, int ab) {
+    return (wb == 4 && ab == 4) || (wb == 2 && ab == 4) || (wb == 8 && ab == 8);
+}
+
+struct LinearExtra {      // head-major output of the QKV linear inside the block
+    int head_major = 0;
+    int D = 0, dh = 0, Ntok = 0, Bimg = 0, Hh = 0;
+    float s_q = 0, s_k = 0, s_v = 0;
+    uint8_t *dst = nullptr; int sb = 0; int bits = 0;
+};
+
+// Shared by vq_linear and vq_attention_block; all descriptors already validated.
+vq_status run_linear(const vq_qmat *xq, float s_x, const vq_qmat *wq, const float *s_w,
+                     int per_channel, const float *bias, int act, int32_t *acc_out, float *y_out,
+                     float s_y, const vq_qmat *yq_out, const LinearExtra *ex, hipStream_t stream) {
+    GemmParams p{};
+    p.x = (const uint8_t *)xq->data; p.x_stride = xq->row_stride; p.M = (int)xq->rows;
+    p.w = (const uint8_t *)wq->data; p.w_stride = wq->row_stride; p.Nout = (int)wq->rows;
+    p.K = (int)xq->cols;
+    p.kbytes_x16 = (int)row_bytes16(xq);
+    p.kbytes_w16 = (int)row_bytes16(wq);
+    p.s_x = s_x; p.s_w = s_w; p.s_w_per_channel = per_channel; p.bias = bias; p.act = act;
+    p.acc_out = acc_out; p.y_out = y_out; p.vec_ok = (p.Nout % 4 == 0) ? 1 : 0;
+    if (((uintptr_t)acc_out) % 16 || ((uintptr_t)y_out) % 16) p.vec_ok = 0;
+    if (ex && ex->head_major) {
+        p.head_major = 1;
+        p.D = ex->D; p.dh = ex->dh; p.Ntok = ex->Ntok; p.Bimg = ex->Bimg; p.Hh = ex->Hh;
+        p.s_y[0] = ex->s_q; p.s_y[1] = ex->s_k; p.s_y[2] = ex->s_v;
+        p.yq = ex->dst; p.yq_sb = ex->sb; p.yq_stride = (int64_t)ex->dh * ex->sb / 8;
+        p.yq_row_bytes16 = (int)p.yq_stride;
+        level_range(ex->bits, &p.qminf, &p.qmaxf);
+    } else if (yq_out) {
+        p.yq = (uint8_t *)yq_out->data; p.yq_stride = yq_out->row_stride; p.yq_sb = yq_out->storage_bits;
+        p.yq_row_bytes16 = (int)row_bytes16(yq_out);
+        p.s_y[0] = p.s_y[1] = p.s_y[2] = s_y;
+        level_range(yq_out->bits, &p.qminf, &p.qmaxf);
+    }
+    if (p.M == 0 || p.Nout == 0) return VQ_OK;
+    hipError_t e = gemm_launch(p, wq->storage_bits, xq->storage_bits, stream);
+    return e == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
+vq_status check_linear_operands(const vq_qmat *xq, const vq_qmat *wq) {
+    vq_status st;
+    if ((st = check_qmat(xq, 0)) != VQ_OK) return st;
+    if ((st = check_qmat(wq, 0)) != VQ_OK) return st;
+    if (xq->cols != wq->cols) return VQ_ERR_SHAPE;
+    if (xq->cols > 65536) return VQ_ERR_SHAPE;
+    if (!pair_supported(wq->storage_bits, xq->storage_bits)) return VQ_ERR_UNSUPPORTED;
+    return VQ_OK;
+}
+
+int pick_qsplit(int64_t heads, int N) {
+    const int nqb = (N + 15) / 16;
+    const int max_split = (nqb + 3) / 4;
+    if (heads >= 512) return 1;
+    int64_t want = (512 + heads - 1) / heads;
+    if (want > max_split) want = max_split;
+    return want < 1 ? 1 : (int)want;
+}
+
+// alpha = ((s_q*s_k)*scale)*log2(e) in fp32, then divided by the 2^shift operand factor.
+// The division by a power of two must be exact for the kernel's product to round like the
+// definition's; it is unless alpha is subnormal-small.
+bool scaled_alpha(float s_q, float s_k, float scale, int shift, float *out) {
+    const float kLog2e = 0x1.715476p+0f;
+    float alpha = ((s_q * s_k) * scale) * kLog2e;
+    if (!good_step(alpha)) return false;
+    float scaled = ldexpf(alpha, -shift);
+    if (!(ldexpf(scaled, shift) == alpha) || !isnormal(scaled)) return false;
+    *out = scaled;
+    return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *vq_status_string(vq_status s) {
+    switch (s) {
+        case VQ_OK: return "ok";
+        case VQ_ERR_NULL: return "required pointer is NULL";
+        case VQ_ERR_SHAPE: return "bad or mismatching dimensions";
+        case VQ_ERR_BITS: return "bad bit width / storage width / signedness";
+        case VQ_ERR_STRIDE: return "row stride too small or stride/pointer not 16-byte aligned";
+        case VQ_ERR_STEP: return "step size not a positive finite number";
+        case VQ_ERR_UNSUPPORTED: return "no kernel for this combination";
+        case VQ_ERR_WORKSPACE: return "workspace missing or too small";
+        case VQ_ERR_HIP: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+vq_status vq_weight_steps(const float *w, int64_t rows, int64_t cols, int64_t ld, int32_t bits,
+                          float *step_out, void *stream) {
+    if (rows < 0 || cols <= 0 || ld < cols) return VQ_ERR_SHAPE;
+    if (bits < 2 || bits > 8) return VQ_ERR_BITS;
+    if (rows == 0) return VQ_OK;
+    if (!w || !step_out) return VQ_ERR_NULL;
+    float qminf, qmaxf;
+    level_range(bits, &qminf, &qmaxf);
+    hipError_t e = weight_steps_launch(w, rows, cols, ld, qmaxf, step_out, (hipStream_t)stream);
+    return e == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
+vq_status vq_quantize(const float *x, int64_t rows, int64_t cols, int64_t ld, float step,
+                      const float *step_per_row, const vq_qmat *out, void *stream) {
+    vq_status st = check_qmat(out, 0);
+    if (st != VQ_OK) return st;
+    if (rows < 0 || cols <= 0 || ld < cols) return VQ_ERR_SHAPE;
+    if (out->rows != rows || out->cols != cols) return VQ_ERR_SHAPE;
+    if (!step_per_row && !good_step(step)) return VQ_ERR_STEP;
+    if (rows == 0) return VQ_OK;
+    if (!x) return VQ_ERR_NULL;
+    QuantParams p{};
+    p.x = x; p.rows = rows; p.cols = cols; p.ld = ld; p.step = step; p.step_per_row = step_per_row;
+    p.out = (uint8_t *)out->data; p.out_stride = out->row_stride; p.sb = out->storage_bits;
+    p.row_bytes16 = (int)row_bytes16(out);
+    level_range(out->bits, &p.qminf, &p.qmaxf);
+    hipError_t e = quantize_launch(p, (hipStream_t)stream);
+    return e == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
+vq_status vq_linear(const vq_qmat *xq, float s_x, const vq_qmat *wq, const float *s_w,
+                    int32_t s_w_per_channel, const float *bias, int32_t act, int32_t *acc_out,
+                    float *y_out, float s_y, const vq_qmat *yq_out, void *stream) {
+    vq_status st = check_linear_operands(xq, wq);
+    if (st != VQ_OK) return st;
+    if (!s_w) return VQ_ERR_NULL;
+    if (!acc_out && !y_out && !yq_out) return VQ_ERR_NULL;
+    if (act != 0 && act != 1) return VQ_ERR_UNSUPPORTED;
+    if (!good_step(s_x)) return VQ_ERR_STEP;
+    if (yq_out) {
+        if ((st = check_qmat(yq_out, 0)) != VQ_OK) return st;
+        if (yq_out->rows != xq->rows || yq_out->cols != wq->rows) return VQ_ERR_SHAPE;
+        if (!good_step(s_y)) return VQ_ERR_STEP;
+    }
+    return run_linear(xq, s_x, wq, s_w, s_w_per_channel ? 1 : 0, bias, act, acc_out, y_out, s_y, yq_out,
+                      nullptr, (hipStream_t)stream);
+}
+
+vq_status vq_matmul_qk(const vq_qmat *q, const vq_qmat *k, int32_t B, int32_t H, int32_t N,
+                       float s_q, float s_k, float scale, int32_t *s_acc_out,
+                       const vq_qmat *p_out, void *stream) {
+    vq_status st;
+    if ((st = check_qmat(q, 0)) != VQ_OK) return st;
+    if ((st = check_qmat(k, 0)) != VQ_OK) return st;
+    if (B < 0 || H <= 0 || N <= 0) return VQ_ERR_SHAPE;
+    const int64_t rows = (int64_t)B * H * N;
+    if (rows > INT32_MAX) return VQ_ERR_SHAPE;
+    if (q->cols != 64 || k->cols != 64) return VQ_ERR_UNSUPPORTED;
+    if (q->rows != rows || k->rows != rows) return VQ_ERR_SHAPE;
+    if (q->storage_bits != k->storage_bits) return VQ_ERR_BITS;
+    if (q->storage_bits != 4 && q->storage_bits != 8) return VQ_ERR_UNSUPPORTED;
+    if (N > 592) return VQ_ERR_UNSUPPORTED;
+    if (!s_acc_out && !p_out) return VQ_ERR_NULL;
+    if (!good_step(s_q) || !good_step(s_k) || !good_step(scale)) return VQ_ERR_STEP;
+    AttnParams p{};
+    p.pmax = 15; p.p_sb = 4;
+    if (p_out) {
+        if ((st = check_qmat(p_out, 1)) != VQ_OK) return st;
+        if (p_out->rows != rows || p_out->cols != N) return VQ_ERR_SHAPE;
+        if (p_out->storage_bits != 4 && p_out->storage_bits != 8) return VQ_ERR_UNSUPPORTED;
+        p.pmax = (1 << p_out->bits) - 1;
+        p.p_sb = p_out->storage_bits;
+        p.p_out = (uint8_t *)p_out->data; p.p_out_stride = p_out->row_stride;
+        p.p_out_row_bytes16 = (int)row_bytes16(p_out);
+    }
+    if (!scaled_alpha(s_q, s_k, scale, q->storage_bits == 4 ? 8 : 0, &p.alpha_scaled)) return VQ_ERR_STEP;
+    if (rows == 0) return VQ_OK;
+    p.q = (const uint8_t *)q->data; p.k = (const uint8_t *)k->data;
+    p.q_stride = q->row_stride; p.k_stride = k->row_stride; p.sb = q->storage_bits;
+    p.B = B; p.H = H; p.N = N;
+    p.s_acc_out = s_acc_out;
+    p.qsplit = pick_qsplit((int64_t)B * H, N);
+    hipError_t e = attention_launch(p, kAttnQKOnly, (hipStream_t)stream);
+    return e == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
+vq_status vq_matmul_pv(const vq_qmat *pm, const vq_qmat *v, int32_t B, int32_t H, int32_t N,
+                       float s_p, float s_v, int32_t *o_acc_out, float *o_out, float s_o,
+                       const vq_qmat *oq_out, void *stream) {
+    vq_status st;
+    if ((st = check_qmat(pm, 1)) != VQ_OK) return st;
+    if ((st = check_qmat(v, 0)) != VQ_OK) return st;
+    if (B < 0 || H <= 0 || N <= 0) return VQ_ERR_SHAPE;
+    const int64_t rows = (int64_t)B * H * N;
+    if (rows > INT32_MAX) return VQ_ERR_SHAPE;
+    if (v->cols != 64) return VQ_ERR_UNSUPPORTED;
+    if (v->rows != rows || pm->rows != rows || pm->cols != N) return VQ_ERR_SHAPE;
+    if (v->storage_bits != 4 && v->storage_bits != 8) return VQ_ERR_UNSUPPORTED;
+    if (pm->storage_bits != 4 && pm->storage_bits != 8) return VQ_ERR_UNSUPPORTED;
+    if (N > 592) return VQ_ERR_UNSUPPORTED;
+    if (!o_acc_out && !o_out && !oq_out) return VQ_ERR_NULL;
+    if (!good_step(s_p) || !good_step(s_v)) return VQ_ERR_STEP;
+    if (((uintptr_t)o_acc_out) % 16 || ((uintptr_t)o_out) % 16) return VQ_ERR_STRIDE;
+    AttnParams p{};
+    if (oq_out) {
+        if ((st = check_qmat(oq_out, 0)) != VQ_OK) return st;
+        if (oq_out->rows != (int64_t)B * N || oq_out->cols != (int64_t)H * 64) return VQ_ERR_SHAPE;
+        if (oq_out->storage_bits != 4 && oq_out->storage_bits != 8) return VQ_ERR_UNSUPPORTED;
+        if (!good_step(s_o)) return VQ_ERR_STEP;
+        p.oq = (uint8_t *)oq_out->data; p.oq_stride = oq_out->row_stride; p.oq_sb = oq_out->storage_bits;
+        level_range(oq_out->bits, &p.qminf, &p.qmaxf);
+        p.s_o = s_o;
+    } else {
+        p.s_o = 1.0f; p.qminf = -8.0f; p.qmaxf = 7.0f;
+    }
+    if (rows == 0) return VQ_OK;
+    p.v = (const uint8_t *)v->data; p.v_stride = v->row_stride; p.sb = v->storage_bits;
+    p.p_in = (const uint8_t *)pm->data; p.p_in_stride = pm->row_stride;
+    p.p_in_row_bytes16 = (int)row_bytes16(pm);
+    p.p_sb = pm->storage_bits; p.pmax = (1 << pm->bits) - 1;
+    p.B = B; p.H = H; p.N = N;
+    p.spv = s_p * s_v;
+    p.o_acc_out = o_acc_out; p.o_out = o_out;
+    p.qsplit = pick_qsplit((int64_t)B * H, N);
+    hipError_t e = attention_launch(p, kAttnPVOnly, (hipStream_t)stream);
+    return e == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
+// ---- the whole block ----------------------------------------------------------------------
+
+namespace {
+
+struct BlockLayout {
+    int64_t M; int sa; int dh;
+    size_t qkv_off, o_off, x2_off, h_off, total;
+    int64_t qkv_bytes, act_row, h_row;
+};
+
+size_t align256(size_t v) { return (v + 255) / 256 * 256; }
+
+vq_status block_check(const vq_block_desc *d, int64_t B, BlockLayout *L) {
+    if (!d) return VQ_ERR_NULL;
+    if (d->D <= 0 || d->H <= 0 || d->N <= 0 || d->hidden < 0 || B < 0) return VQ_ERR_SHAPE;
+    if (d->D % d->H != 0) return VQ_ERR_SHAPE;
+    if (d->D / d->H != 64) return VQ_ERR_UNSUPPORTED;
+    if (d->N > 592) return VQ_ERR_UNSUPPORTED;
+    if (d->hidden % 64 != 0) return VQ_ERR_SHAPE;
+    if (d->storage_a != 4 && d->storage_a != 8) return VQ_ERR_BITS;
+    if (d->bits_a < 2 || d->bits_a > d->storage_a) return VQ_ERR_BITS;
+    if (d->bits_p < 2 || d->bits_p > d->storage_a) return VQ_ERR_BITS;
+    if ((int64_t)B * d->N > INT32_MAX / 4 || (int64_t)B * d->H * d->N > INT32_MAX / 4) return VQ_ERR_SHAPE;
+    L->M = B * d->N; L->sa = d->storage_a; L->dh = 64;
+    L->act_row = (int64_t)d->D * L->sa / 8;
+    L->h_row = (int64_t)d->hidden * L->sa / 8;
+    L->qkv_bytes = 3 * B * d->H * d->N * (64 * L->sa / 8);
+    size_t off = 0;
+    L->qkv_off = off; off += align256((size_t)L->qkv_bytes);
+    L->o_off = off;   off += align256((size_t)(L->M * L->act_row));
+    L->x2_off = off;  off += d->hidden ? align256((size_t)(L->M * L->act_row)) : 0;
+    L->h_off = off;   off += d->hidden ? align256((size_t)(L->M * L->h_row)) : 0;
+    L->total = off;
+    return VQ_OK;
+}
+
+vq_status weight_check(const vq_qmat *w, int64_t rows, int64_t cols, int sa, const float *sw) {
+    vq_status st = check_qmat(w, 0);
+    if (st != VQ_OK) return st;
+    if (w->rows != rows || w->cols != cols) return VQ_ERR_SHAPE;
+    if (!pair_supported(w->storage_bits, sa)) return VQ_ERR_UNSUPPORTED;
+    if (!sw) return VQ_ERR_NULL;
+    return VQ_OK;
+}
+
+}  // namespace
+
+vq_status vq_attention_block_workspace(const vq_block_desc *desc, int64_t B, size_t *bytes) {
+    if (!bytes) return VQ_ERR_NULL;
+    BlockLayout L;
+    vq_status st = block_check(desc, B, &L);
+    if (st != VQ_OK) return st;
+    *bytes = L.total;
+    return VQ_OK;
+}
+
+vq_status vq_attention_block(const vq_block_desc *d, const vq_qmat *xq, int64_t B, float *y_out,
+                             void *workspace, size_t workspace_bytes, void *stream_) {
+    BlockLayout L;
+    vq_status st = block_check(d, B, &L);
+    if (st != VQ_OK) return st;
+    hipStream_t stream = (hipStream_t)stream_;
+    if ((st = check_qmat(xq, 0)) != VQ_OK) return st;
+    if (xq->rows != L.M || xq->cols != d->D || xq->storage_bits != L.sa) return VQ_ERR_SHAPE;
+    if ((st = weight_check(&d->w_qkv, 3 * (int64_t)d->D, d->D, L.sa, d->sw_qkv)) != VQ_OK) return st;
+    if ((st = weight_check(&d->w_proj, d->D, d->D, L.sa, d->sw_proj)) != VQ_OK) return st;
+    if (d->hidden) {
+        if ((st = weight_check(&d->w_fc1, d->hidden, d->D, L.sa, d->sw_fc1)) != VQ_OK) return st;
+        if ((st = weight_check(&d->w_fc2, d->D, d->hidden, L.sa, d->sw_fc2)) != VQ_OK) return st;
+        if (!good_step(d->s_x2) || !good_step(d->s_h)) return VQ_ERR_STEP;
+    }
+    if (!good_step(d->s_x) || !good_step(d->s_q) || !good_step(d->s_k) || !good_step(d->s_v) ||
+        !good_step(d->s_o) || !good_step(d->scale))
+        return VQ_ERR_STEP;
+    float alpha_scaled;
+    if (!scaled_alpha(d->s_q, d->s_k, d->scale, L.sa == 4 ? 8 : 0, &alpha_scaled)) return VQ_ERR_STEP;
+    if (B == 0) return VQ_OK;
+    if (!y_out) return VQ_ERR_NULL;
+    if (!workspace || workspace_bytes < L.total) return VQ_ERR_WORKSPACE;
+    if (((uintptr_t)workspace) % 256 != 0) return VQ_ERR_WORKSPACE;
+    if (((uintptr_t)y_out) % 16 != 0) return VQ_ERR_STRIDE;
+    for (void *dp : {d->dump_qkv, d->dump_o, d->dump_x2, d->dump_h})
+        if (((uintptr_t)dp) % 16 != 0) return VQ_ERR_STRIDE;
+
+    uint8_t *ws = (uint8_t *)workspace;
+    uint8_t *qkv = d->dump_qkv ? (uint8_t *)d->dump_qkv : ws + L.qkv_off;
+    uint8_t *obuf = d->dump_o ? (uint8_t *)d->dump_o : ws + L.o_off;
+    uint8_t *x2buf = d->dump_x2 ? (uint8_t *)d->dump_x2 : ws + L.x2_off;
+    uint8_t *hbuf = d->dump_h ? (uint8_t *)d->dump_h : ws + L.h_off;
+    const int64_t BHN = B * d->H * d->N;
+    const int64_t hrow = 64 * L.sa / 8;
+
+    // 1. QKV linear; the epilogue requantizes Q, K, V with their own steps, head-major
+    LinearExtra ex;
+    ex.head_major = 1; ex.D = d->D; ex.dh = 64; ex.Ntok = d->N; ex.Bimg = (int)B; ex.Hh = d->H;
+    ex.s_q = d->s_q; ex.s_k = d->s_k; ex.s_v = d->s_v; ex.dst = qkv; ex.sb = L.sa; ex.bits = d->bits_a;
+    st = run_linear(xq, d->s_x, &d->w_qkv, d->sw_qkv, 1, d->b_qkv, 0, nullptr, nullptr, 0.0f, nullptr, &ex,
+                    stream);
+    if (st != VQ_OK) return st;
+
+    // 2. fused attention: scores and P never leave the chip
+    vq_qmat oq{};
+    oq.data = obuf; oq.bits = d->bits_a; oq.storage_bits = L.sa; oq.rows = L.M; oq.cols = d->D;
+    oq.row_stride = L.act_row;
+    {
+        AttnParams p{};
+        p.q = qkv; p.k = qkv + BHN * hrow; p.v = qkv + 2 * BHN * hrow;
+        p.q_stride = p.k_stride = p.v_stride = hrow;
+        p.sb = L.sa; p.B = (int)B; p.H = d->H; p.N = d->N;
+        p.alpha_scaled = alpha_scaled;
+        p.pmax = (1 << d->bits_p) - 1;
+        p.p_sb = L.sa;
+        p.spv = (1.0f / (float)p.pmax) * d->s_v;
+        p.s_o = d->s_o;
+        level_range(d->bits_a, &p.qminf, &p.qmaxf);
+        p.oq = obuf; p.oq_stride = L.act_row; p.oq_sb = L.sa;
+        p.qsplit = pick_qsplit((int64_t)B * d->H, d->N);
+        if (attention_launch(p, kAttnFused, stream) != hipSuccess) return VQ_ERR_HIP;
+    }
+
+    // 3. projection (fp32 out, or requantized for the MLP)
+    if (!d->hidden)
+        return run_linear(&oq, d->s_o, &d->w_proj, d->sw_proj, 1, d->b_proj, 0, nullptr, y_out, 0.0f, nullptr,
+                          nullptr, stream);
+    vq_qmat x2{};
+    x2.data = x2buf; x2.bits = d->bits_a; x2.storage_bits = L.sa; x2.rows = L.M; x2.cols = d->D;
+    x2.row_stride = L.act_row;
+    st = run_linear(&oq, d->s_o, &d->w_proj, d->sw_proj, 1, d->b_proj, 0, nullptr, nullptr, d->s_x2, &x2, nullptr,
+                    stream);
+    if (st != VQ_OK) return st;
+    // 4. fc1 + GELU + requant, 5. fc2
+    vq_qmat hq{};
+    hq.data = hbuf; hq.bits = d->bits_a; hq.storage_bits = L.sa; hq.rows = L.M; hq.cols = d->hidden;
+    hq.row_stride = L.h_row;
+    st = run_linear(&x2, d->s_x2, &d->w_fc1, d->sw_fc1, 1, d->b_fc1, 1, nullptr, nullptr, d->s_h, &hq, nullptr,
+                    stream);
+    if (st != VQ_OK) return st;
+    return run_linear(&hq, d->s_h, &d->w_fc2, d->sw_fc2, 1, d->b_fc2, 0, nullptr, y_out, 0.0f, nullptr, nullptr,
+                      stream);
+}
+
+}  // extern "C"

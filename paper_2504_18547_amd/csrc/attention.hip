@@ -1,0 +1,341 @@
+// Attention on quantized operands: S = Q.K^T (Eq. 3), shift-based exponential (Eq. 4), the
+// softmax division absorbed into the P quantizer's thresholds (Sec. IV-B), and O = P.V with
+// the operand scales applied next to the output quantizer (Sec. IV-B).
+//
+// One workgroup (4 waves) serves one (image, head): K (packed) and V^T (int8) are staged in
+// LDS once, then each wave takes blocks of 16 query rows.  Everything between the two
+// matmuls stays in registers:
+//
+//   S^T tile = mfma_16x16x64(A = K rows, B = Q rows)  -> lane (query = lane%16, g = lane/16)
+//              holds keys 16t + 4g + r of tile t: a full score row lives in 4 lanes, so the
+//              integer row max and row sum are in-register reductions plus two lane swaps.
+//   P^T      = the quantized levels, packed 4 per register in exactly the order the second
+//              MFMA wants for its B operand (no LDS round trip between the matmuls).
+//   O^T tile = mfma_16x16x64(A = V^T rows, B = P^T)   -> lane holds 16 consecutive d of its
+//              query: one 8-byte packed store per lane.
+//
+// All reductions are integer, so lane order cannot change a result.
+#include "attention.h"
+#include "vitq_dev.h"
+
+namespace vitq {
+
+namespace {
+
+// physical LDS row of V^T column d: the sixteen rows one MFMA reads are consecutive
+__device__ __forceinline__ int vt_row(int d) { return 16 * ((d >> 2) & 3) + 4 * (d >> 4) + (d & 3); }
+// position of key n inside a V^T row: lane group g = (n%16)/4 owns 16 consecutive bytes of
+// every 64-key chunk, ordered (tile within chunk, r)
+__device__ __forceinline__ int vt_pos(int n) {
+    return (n & ~63) + (((n & 15) >> 2) << 4) + (((n & 63) >> 4) << 2) + (n & 3);
+}
+
+template <int NT, int SB, int MODE, bool P8>
+__global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
+    constexpr int NCH = (NT + 3) / 4;                 // 64-key chunks of the P.V contraction
+    constexpr int NKEYP = NCH * 64;                   // padded key count of V^T rows
+    constexpr int KROW = 64 * SB / 8;                 // bytes of one packed K row
+    constexpr int KPITCH = (SB == 4) ? 40 : 80;       // bank-conflict-free pitch for the fragment reads
+    constexpr int VPITCH = NKEYP + 16;
+    constexpr int SHIFT = (SB == 4) ? 8 : 0;          // both operands of S carry a factor 16 at 4 bits
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    uint8_t *sK = smem;                               // [NT*16][KPITCH]
+    uint8_t *sVT = smem + ((NT * 16 * KPITCH + 15) & ~15);  // [64][VPITCH] int8
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int li = lane & 15;
+    const int g = lane >> 4;
+    const int bh = blockIdx.x;
+    const int b = bh / p.H;
+    const int h = bh - b * p.H;
+    const int N = p.N;
+    const int64_t row0 = (int64_t)bh * N;             // first row of this head in q/k/v/p
+
+    // ---- stage K (packed) and V^T (int8) ---------------------------------------------------
+    if constexpr (MODE != kAttnPVOnly) {
+        constexpr int CH = KROW / 8;                  // 8-byte pieces per row
+        for (int id = tid; id < NT * 16 * CH; id += 256) {
+            int n = id / CH, c = id - n * CH;
+            uint2 v = make_uint2(0, 0);
+            if (n < N) v = *reinterpret_cast<const uint2 *>(p.k + (row0 + n) * p.k_stride + c * 8);
+            *reinterpret_cast<uint2 *>(sK + n * KPITCH + c * 8) = v;
+        }
+    }
+    if constexpr (MODE != kAttnQKOnly) {
+        constexpr int CH = KROW / 16;                 // 16-byte pieces per row
+        for (int id = tid; id < NKEYP * CH; id += 256) {
+            int n = id / CH, c = id - n * CH;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (n < N) v = *reinterpret_cast<const uint4 *>(p.v + (row0 + n) * p.v_stride + c * 16);
+            const u32 w[4] = {v.x, v.y, v.z, v.w};
+            const int pos = vt_pos(n);
+            if constexpr (SB == 4) {
+#pragma unroll
+                for (int j = 0; j < 32; ++j) {
+                    int val = ((int)(w[j >> 3] << (28 - 4 * (j & 7)))) >> 28;   // sign-extended nibble
+                    sVT[vt_row(32 * c + j) * VPITCH + pos] = (uint8_t)val;
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 16; ++j)
+                    sVT[vt_row(16 * c + j) * VPITCH + pos] = (uint8_t)(w[j >> 2] >> (8 * (j & 3)));
+            }
+        }
+    }
+    __syncthreads();
+
+    const int nqb = (N + 15) / 16;
+    const int wslot = (wave + bh) & 3;                // rotate which wave gets the odd block
+    for (int qb = blockIdx.y * 4 + wslot; qb < nqb; qb += 4 * p.qsplit) {
+        const int qrow = qb * 16 + li;                // query row of this lane
+        const bool qok = qrow < N;
+        u32 pp[NCH * 4];                              // packed P^T: 4 levels per register
+#pragma unroll
+        for (int i = 0; i < NCH * 4; ++i) pp[i] = P8 ? 0x80808080u : 0u;
+
+        if constexpr (MODE != kAttnPVOnly) {
+            // ---- S^T = K . Q^T ------------------------------------------------------------
+            v4i qf;
+            {
+                const uint8_t *src = p.q + (row0 + qrow) * p.q_stride;
+                if constexpr (SB == 4) {
+                    uint2 v = make_uint2(0, 0);
+                    if (qok) v = *reinterpret_cast<const uint2 *>(src + 8 * g);
+                    qf = unpack4_x16(v.x, v.y);
+                } else {
+                    uint4 v = make_uint4(0, 0, 0, 0);
+                    if (qok) v = *reinterpret_cast<const uint4 *>(src + 16 * g);
+                    qf[0] = (int)v.x; qf[1] = (int)v.y; qf[2] = (int)v.z; qf[3] = (int)v.w;
+                }
+            }
+            v4i s[NT];
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                v4i kf;
+                const uint8_t *src = sK + (16 * t + li) * KPITCH;
+                if constexpr (SB == 4) {
+                    uint2 v = *reinterpret_cast<const uint2 *>(src + 8 * g);
+                    kf = unpack4_x16(v.x, v.y);
+                } else {
+                    kf = *reinterpret_cast<const v4i *>(src + 16 * g);
+                }
+                v4i z = {0, 0, 0, 0};
+                s[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(kf, qf, z, 0, 0, 0);
+            }
+            // ---- integer row max (keys >= N excluded) ---------------------------------------
+            int mx = INT32_MIN;
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int key = 16 * t + 4 * g + r;
+                    if (key < N) mx = max(mx, s[t][r]);
+                }
+            mx = max(mx, __shfl_xor(mx, 16, 64));
+            mx = max(mx, __shfl_xor(mx, 32, 64));
+            if constexpr (MODE == kAttnQKOnly) {
+                if (p.s_acc_out && qok) {
+                    int32_t *dst = p.s_acc_out + (row0 + qrow) * N;
+#pragma unroll
+                    for (int t = 0; t < NT; ++t)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const int key = 16 * t + 4 * g + r;
+                            if (key < N) dst[key] = s[t][r] >> SHIFT;
+                        }
+                }
+            }
+            // ---- shift-based exponential in 12.20 fixed point, integer row sum --------------
+            u32 sum = 0;
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int key = 16 * t + 4 * g + r;
+                    u32 e = 0;
+                    if (key < N) {
+                        float tt = p.alpha_scaled * (float)(s[t][r] - mx);
+                        float f = floorf(tt);
+                        float fr = tt - f;
+                        u32 u = (u32)((1.0f + fr) * 1048576.0f);
+                        float nf = -f;
+                        int sh = (nf >= 31.0f) ? 31 : (int)nf;
+                        e = u >> sh;
+                    }
+                    s[t][r] = (int)e;
+                    sum += e;
+                }
+            sum += __shfl_xor(sum, 16, 64);
+            sum += __shfl_xor(sum, 32, 64);
+            // ---- P level = #{k : 2*pmax*e > (2k-1)*sum}: float estimate, exact integer fix-up -
+            const float inv = (float)p.pmax / (float)sum;
+            const u32 two_pmax = 2u * (u32)p.pmax;
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                u32 packed = 0;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const u32 e = (u32)s[t][r];
+                    u32 c = (u32)rintf((float)e * inv);
+                    const uint64_t lhs = (uint64_t)two_pmax * e;
+                    const uint64_t up = (uint64_t)(2u * c + 1u) * sum;
+                    const uint64_t dn = (uint64_t)(2u * c - 1u) * sum;   // only used when c > 0
+                    if (lhs > up) c += 1;
+                    else if (c > 0 && lhs <= dn) c -= 1;
+                    c = min(c, (u32)p.pmax);
+                    packed |= (P8 ? (c ^ 0x80u) : c) << (8 * r);
+                }
+                pp[t] = packed;
+            }
+            if constexpr (MODE == kAttnQKOnly) {
+                if (p.p_out && qok) {
+                    uint8_t *dst = p.p_out + (row0 + qrow) * p.p_out_stride;
+#pragma unroll
+                    for (int t = 0; t < NT + 1; ++t) {
+                        const u32 lv = (t < NT) ? (P8 ? (pp[t < NT ? t : 0] ^ 0x80808080u) : pp[t < NT ? t : 0]) : 0u;
+                        if (p.p_sb == 4) {
+                            const int off = 8 * t + 2 * g;
+                            if (off < p.p_out_row_bytes16) {
+                                u32 hw = (lv & 0xFu) | ((lv >> 4) & 0xF0u) | ((lv >> 8) & 0xF00u) | ((lv >> 12) & 0xF000u);
+                                *reinterpret_cast<uint16_t *>(dst + off) = (uint16_t)hw;
+                            }
+                        } else {
+                            const int off = 16 * t + 4 * g;
+                            if (off < p.p_out_row_bytes16) *reinterpret_cast<u32 *>(dst + off) = lv;
+                        }
+                    }
+                }
+            }
+        } else {
+            // ---- P^T from memory (stand-alone P.V) ------------------------------------------
+            const uint8_t *src = p.p_in + (row0 + qrow) * p.p_in_stride;
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                u32 lv = 0;
+                if (p.p_sb == 4) {
+                    const int off = 8 * t + 2 * g;
+                    if (qok && off < p.p_in_row_bytes16) {
+                        u32 hw = *reinterpret_cast<const uint16_t *>(src + off);
+                        lv = (hw & 0xFu) | ((hw & 0xF0u) << 4) | ((hw & 0xF00u) << 8) | ((hw & 0xF000u) << 12);
+                    }
+                } else {
+                    const int off = 16 * t + 4 * g;
+                    if (qok && off < p.p_in_row_bytes16) lv = *reinterpret_cast<const u32 *>(src + off);
+                }
+                pp[t] = P8 ? (lv ^ 0x80808080u) : lv;
+            }
+        }
+
+        if constexpr (MODE != kAttnQKOnly) {
+            // ---- O^T = V^T . P^T ------------------------------------------------------------
+            v4i o[4], cs[4];
+#pragma unroll
+            for (int T = 0; T < 4; ++T) { o[T] = v4i{0, 0, 0, 0}; cs[T] = v4i{0, 0, 0, 0}; }
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                v4i pf;
+                pf[0] = (int)pp[4 * c]; pf[1] = (int)pp[4 * c + 1];
+                pf[2] = (int)pp[4 * c + 2]; pf[3] = (int)pp[4 * c + 3];
+#pragma unroll
+                for (int T = 0; T < 4; ++T) {
+                    v4i vf = *reinterpret_cast<const v4i *>(sVT + (16 * T + li) * VPITCH + 64 * c + 16 * g);
+                    o[T] = __builtin_amdgcn_mfma_i32_16x16x64_i8(vf, pf, o[T], 0, 0, 0);
+                    if constexpr (P8) {
+                        // levels are stored minus 128; add 128 * (column sum of V) back
+                        const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
+                        cs[T] = __builtin_amdgcn_mfma_i32_16x16x64_i8(vf, ones, cs[T], 0, 0, 0);
+                    }
+                }
+            }
+            if (qok) {
+                int q16[16];
+                float of[16];
+                int oa[16];
+#pragma unroll
+                for (int T = 0; T < 4; ++T)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        int a = o[T][r];
+                        if constexpr (P8) a += 128 * cs[T][r];
+                        oa[4 * T + r] = a;
+                        float ov = (float)a * p.spv;
+                        of[4 * T + r] = ov;
+                        q16[4 * T + r] = quantize_level(ov, p.s_o, p.qminf, p.qmaxf);
+                    }
+                const int d0 = 16 * g;
+                if (p.o_acc_out) {
+                    int4 *dst = reinterpret_cast<int4 *>(p.o_acc_out + (row0 + qrow) * 64 + d0);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) dst[j] = make_int4(oa[4 * j], oa[4 * j + 1], oa[4 * j + 2], oa[4 * j + 3]);
+                }
+                const int64_t orow = (int64_t)b * N + qrow;
+                if (p.o_out) {
+                    float4 *dst = reinterpret_cast<float4 *>(p.o_out + orow * (p.H * 64) + h * 64 + d0);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) dst[j] = make_float4(of[4 * j], of[4 * j + 1], of[4 * j + 2], of[4 * j + 3]);
+                }
+                if (p.oq) {
+                    uint8_t *dst = p.oq + orow * p.oq_stride + (((h * 64 + d0) * p.oq_sb) >> 3);
+                    u32 w[4];
+                    if (p.oq_sb == 4) {
+                        pack16<4>(q16, w);
+                        *reinterpret_cast<uint2 *>(dst) = make_uint2(w[0], w[1]);
+                    } else {
+                        pack16<8>(q16, w);
+                        *reinterpret_cast<uint4 *>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int NT, int SB, int MODE, bool P8>
+hipError_t launch_one(const AttnParams &p, hipStream_t stream) {
+    constexpr int NCH = (NT + 3) / 4;
+    constexpr int KPITCH = (SB == 4) ? 40 : 80;
+    constexpr size_t lds = ((NT * 16 * KPITCH + 15) & ~15) + (size_t)64 * (NCH * 64 + 16);
+    auto kern = attention_kernel<NT, SB, MODE, P8>;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    dim3 grid((unsigned)(p.B * p.H), (unsigned)p.qsplit);
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, stream, p);
+    return hipGetLastError();
+}
+
+template <int NT, int SB, int MODE>
+hipError_t launch_p(const AttnParams &p, hipStream_t stream) {
+    if (p.pmax > 127) return launch_one<NT, SB, MODE, true>(p, stream);
+    return launch_one<NT, SB, MODE, false>(p, stream);
+}
+
+template <int NT, int SB>
+hipError_t launch_mode(const AttnParams &p, AttnMode mode, hipStream_t stream) {
+    switch (mode) {
+        case kAttnFused: return launch_p<NT, SB, kAttnFused>(p, stream);
+        case kAttnQKOnly: return launch_p<NT, SB, kAttnQKOnly>(p, stream);
+        case kAttnPVOnly: return launch_p<NT, SB, kAttnPVOnly>(p, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+hipError_t attention_launch(const AttnParams &p, AttnMode mode, hipStream_t stream) {
+    if (p.B * p.H == 0) return hipSuccess;
+    if (p.N <= 13 * 16) {
+        if (p.sb == 4) return launch_mode<13, 4>(p, mode, stream);
+        if (p.sb == 8) return launch_mode<13, 8>(p, mode, stream);
+    } else if (p.N <= 37 * 16) {
+        if (p.sb == 4) return launch_mode<37, 4>(p, mode, stream);
+        if (p.sb == 8) return launch_mode<37, 8>(p, mode, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace vitq

@@ -1,0 +1,27 @@
+// Host-visible parameter block and launcher of the integer GEMM kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace vitq {
+
+struct GemmParams {
+    // operands (packed along K)
+    const uint8_t *x; int64_t x_stride; int M;       // tokens    [M x K]
+    const uint8_t *w; int64_t w_stride; int Nout;    // weights   [Nout x K]
+    int K;
+    int kbytes_x16, kbytes_w16;                      // valid bytes per row, rounded up to 16
+    // dequantization
+    float s_x; const float *s_w; int s_w_per_channel; const float *bias; int act;
+    // outputs (each nullable)
+    int32_t *acc_out; float *y_out; int vec_ok;      // vec_ok: Nout % 4 == 0 (aligned rows)
+    uint8_t *yq; int64_t yq_stride; int yq_sb; int yq_row_bytes16;
+    float s_y[3]; float qminf, qmaxf;
+    // head-major output of the QKV linear: channel -> (q/k/v, head, d), token -> (image, n)
+    int head_major; int D, dh, Ntok, Bimg, Hh;
+};
+
+// wb / ab: storage bits of the weight / activation operand.  Supported: (4,4) (2,4) (8,8).
+hipError_t gemm_launch(const GemmParams &p, int wb, int ab, hipStream_t stream);
+
+}  // namespace vitq

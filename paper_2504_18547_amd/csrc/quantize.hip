@@ -1,0 +1,86 @@
+// Uniform b-bit quantizer writing the packed format, and the absmax weight-step rule.
+// Both are streaming kernels bound by HBM: the quantizer reads 4 bytes and writes b/8 bytes
+// per element.
+#include "quantize.h"
+#include "vitq_dev.h"
+
+namespace vitq {
+
+namespace {
+
+// One thread produces one 32-bit word of a packed row (32/SB consecutive levels), so a wave
+// reads a contiguous run of fp32 values and writes 256 contiguous bytes.
+template <int SB>
+__global__ __launch_bounds__(256) void quantize_kernel(QuantParams p) {
+    constexpr int PER = 32 / SB;
+    const int words_per_row = p.row_bytes16 / 4;
+    const int64_t total = p.rows * words_per_row;
+    for (int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; id < total;
+         id += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t r = id / words_per_row;
+        const int wi = (int)(id - r * words_per_row);
+        const float s = p.step_per_row ? p.step_per_row[r] : p.step;
+        const float *src = p.x + r * p.ld;
+        const int64_t c0 = (int64_t)wi * PER;
+        u32 word = 0;
+        if (c0 + PER <= p.cols && (((uintptr_t)(src + c0)) & 15) == 0) {
+#pragma unroll
+            for (int j = 0; j < PER / 4; ++j) {
+                float4 v = reinterpret_cast<const float4 *>(src + c0)[j];
+                const float f[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    int q = quantize_level(f[i], s, p.qminf, p.qmaxf);
+                    word |= ((u32)q & ((1u << SB) - 1u)) << (SB * (4 * j + i));
+                }
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                if (c0 + i < p.cols) {
+                    int q = quantize_level(src[c0 + i], s, p.qminf, p.qmaxf);
+                    word |= ((u32)q & ((1u << SB) - 1u)) << (SB * i);
+                }
+            }
+        }
+        *reinterpret_cast<u32 *>(p.out + r * p.out_stride + (int64_t)wi * 4) = word;
+    }
+}
+
+// One wave per row: max |w| by a butterfly over the 64 lanes (max is order-independent).
+__global__ __launch_bounds__(256) void weight_steps_kernel(const float *w, int64_t rows, int64_t cols,
+                                                           int64_t ld, float qmaxf, float *step_out) {
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * (blockDim.x / 64) + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const float *src = w + row * ld;
+    float m = 0.0f;
+    for (int64_t c = lane; c < cols; c += 64) m = fmaxf(m, fabsf(src[c]));
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+    if (lane == 0) step_out[row] = (m == 0.0f) ? 1.0f : m / qmaxf;
+}
+
+}  // namespace
+
+hipError_t quantize_launch(const QuantParams &p, hipStream_t stream) {
+    const int64_t total = p.rows * (p.row_bytes16 / 4);
+    if (total == 0) return hipSuccess;
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    if (p.sb == 4) hipLaunchKernelGGL(quantize_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, stream, p);
+    else if (p.sb == 8) hipLaunchKernelGGL(quantize_kernel<8>, dim3((unsigned)blocks), dim3(256), 0, stream, p);
+    else hipLaunchKernelGGL(quantize_kernel<2>, dim3((unsigned)blocks), dim3(256), 0, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t weight_steps_launch(const float *w, int64_t rows, int64_t cols, int64_t ld, float qmaxf,
+                               float *step_out, hipStream_t stream) {
+    if (rows == 0) return hipSuccess;
+    int64_t blocks = (rows + 3) / 4;
+    hipLaunchKernelGGL(weight_steps_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, w, rows, cols, ld,
+                       qmaxf, step_out);
+    return hipGetLastError();
+}
+
+}  // namespace vitq
