@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the integerized ViT block on one MI355X.
+
+One "step" = one pass of the whole hot path over one batch: vq_quantize of the fp32 tokens to
+packed 4-bit X_q, then vq_attention_block (QKV linear, fused attention, projection, fc1+GELU,
+fc2).  Inputs (fp32 tokens, packed weights, steps, biases) are resident in HBM before the timed
+region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload vit_b_block] [--sharp]
+"""
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "int TOPS (% of int8 MFMA peak) + ViT-B 4-bit attn+MLP block images/sec"
+INT8_MFMA_PEAK_TOPS = 5000.0      # MI355X published dense int8 rate
+HBM_PEAK_GBS = 8000.0
+STAGES = ["qkv", "attention", "proj", "fc1", "fc2"]
+
+
+class Hip:
+    """The few HIP runtime calls the benchmark needs for event timing (the runtime torch loaded)."""
+
+    def __init__(self):
+        import torch
+        path = os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so")
+        self.lib = C.CDLL(path if os.path.exists(path) else "libamdhip64.so")
+        self.lib.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.lib.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]
+        self.lib.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.lib.hipEventDestroy.argtypes = [C.c_void_p]
+
+    def event(self):
+        e = C.c_void_p()
+        assert self.lib.hipEventCreate(C.byref(e)) == 0
+        return e
+
+    def record(self, e, stream):
+        assert self.lib.hipEventRecord(e, C.c_void_p(stream)) == 0
+
+    def elapsed_ms(self, a, b):
+        ms = C.c_float()
+        rc = self.lib.hipEventElapsedTime(C.byref(ms), a, b)
+        assert rc == 0, rc
+        return ms.value
+
+
+def cpu_baseline(name, sharp, bits_w, bits_a, ops_per_image):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload."""
+    import numpy as np
+    from oracle import vqo
+    from paper_2504_18547_amd import workloads as wl
+    threads = min(vqo.num_threads(), 16)
+    dims = wl.block_dims(name)
+    n_img = 12 * threads
+    st = wl.block_steps(name, sharp, bits_w, bits_a)
+    w_fp = wl.block_weights(name, sharp=sharp)
+    wts = {}
+    for nm in ("qkv", "proj", "fc1", "fc2"):
+        if "w_" + nm in w_fp:
+            s = vqo.weight_steps(w_fp["w_" + nm], bits_w)
+            wts["w_" + nm] = vqo.quantize(w_fp["w_" + nm], s, bits_w, per_row=True)
+            wts["sw_" + nm], wts["b_" + nm] = s, w_fp["b_" + nm]
+    tokens = wl.block_tokens(name, list(range(n_img))).reshape(n_img * dims["N"], dims["D"])
+    t0 = time.perf_counter()
+    xq = vqo.quantize(tokens, st["s_x"], bits_a)
+    vqo.attention_block(xq, n_img, dims, wts, st, bits_a=bits_a, bits_p=bits_a, dumps=False, threads=threads)
+    dt = time.perf_counter() - t0
+    ips = n_img / dt
+    return {"value": ips * ops_per_image / 1e12, "unit": "TOPS", "images_per_s": ips, "cores": threads,
+            "kind": "oracle", "seconds": dt,
+            "sample": "%d images of %s through oracle/vqo.c (quantize + whole block), OpenMP over images" % (n_img, name)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="vit_b_block")
+    ap.add_argument("--bits-w", type=int, default=4)
+    ap.add_argument("--bits-a", type=int, default=4)
+    ap.add_argument("--batch", type=int, default=0, help="0 = the batch the configuration is quoted on")
+    ap.add_argument("--sharp", action="store_true", help="sharp-attention variant of the weights")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (every image is independent; see DESIGN.md "
+              "for how the path would shard); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2504_18547_amd import opcount, vitq, workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    vitq.lib()                                   # fails loudly if the HIP library is not built
+    name, bw, ba = args.workload, args.bits_w, args.bits_a
+    dims = wl.block_dims(name)
+    D, H, N, hidden = dims["D"], dims["H"], dims["N"], dims["hidden"]
+    B = args.batch or wl.BLOCKS[name]["batch"]
+    sa = 4 if ba == 3 else ba
+    st = wl.block_steps(name, args.sharp, bw, ba)
+
+    # ---- resident inputs ---------------------------------------------------------------------
+    w_fp = wl.block_weights(name, sharp=args.sharp)
+    wd = {}
+    for nm in ("qkv", "proj", "fc1", "fc2"):
+        if "w_" + nm not in w_fp:
+            continue
+        w = torch.from_numpy(w_fp["w_" + nm]).cuda()
+        s = vitq.vq_weight_steps(w, bw)
+        q = vitq.QMat.empty(w.shape[0], w.shape[1], bw)
+        vitq.vq_quantize(w, 0.0, s, q)
+        wd["w_" + nm], wd["sw_" + nm] = q, s
+        wd["b_" + nm] = torch.from_numpy(w_fp["b_" + nm]).cuda()
+    tokens = torch.empty((B * N, D), dtype=torch.float32, device="cuda")
+    for b0 in range(0, B, 32):
+        imgs = list(range(b0, min(B, b0 + 32)))
+        tokens[b0 * N:(b0 + len(imgs)) * N] = torch.from_numpy(
+            wl.block_tokens(name, imgs).reshape(len(imgs) * N, D)).cuda()
+    xq = vitq.QMat.empty(B * N, D, ba)
+    y = torch.empty((B * N, D), dtype=torch.float32, device="cuda")
+    desc = vitq.make_block_desc(dims, ba, ba, sa, wd, st)
+    ws = torch.empty(vitq.vq_attention_block_workspace(desc, B), dtype=torch.uint8, device="cuda")
+
+    hip = Hip()
+    stream = torch.cuda.current_stream().cuda_stream
+    n_ev = 6 if hidden else 4
+    K, W = args.steps, args.warmup
+    ev_q = [hip.event() for _ in range(K)]
+    ev_sets = [(C.c_void_p * n_ev)(*[hip.event() for _ in range(n_ev)]) for _ in range(K)]
+
+    def step(i=None):
+        if i is not None:
+            hip.record(ev_q[i], stream)
+            desc.stage_events = C.cast(ev_sets[i], C.POINTER(C.c_void_p))
+        else:
+            desc.stage_events = None
+        vitq.vq_quantize(tokens, st["s_x"], None, xq)
+        vitq.vq_attention_block(desc, xq, B, y, ws)
+
+    for _ in range(W):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    # ---- per-stage durations from the events recorded inside the timed region ------------------
+    stage_ms = {"quantize": 0.0}
+    for nm in STAGES[:n_ev - 1]:
+        stage_ms[nm] = 0.0
+    for i in range(K):
+        evs = [C.c_void_p(v) for v in ev_sets[i]]
+        stage_ms["quantize"] += hip.elapsed_ms(ev_q[i], evs[0])
+        for j, nm in enumerate(STAGES[:n_ev - 1]):
+            stage_ms[nm] += hip.elapsed_ms(evs[j], evs[j + 1])
+    stage_ms = {k: v / K for k, v in stage_ms.items()}
+
+    macs = opcount.block_macs(D, H, N, hidden)
+    ops_img = 2 * sum(macs.values())
+    ms_per_step = dt * 1e3 / K
+    ips = B / (dt / K)
+    tops = ips * ops_img / 1e12
+
+    # dominant kernel: the integer GEMM (one kernel, launched once per linear stage)
+    lin = [s for s in ("qkv", "proj", "fc1", "fc2") if s in stage_ms]
+    gemm_ops = 2 * B * sum(macs[s] for s in lin)
+    gemm_ms = sum(stage_ms[s] for s in lin)
+    achieved = gemm_ops / (gemm_ms * 1e-3) / 1e12
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get("%s/w%da%d/b%d" % (name, bw, ba, B))
+    roofline = {"kernel": "gemm_kernel<W%d,A%d> (4 launches per step: qkv, proj, fc1, fc2)" % (bw, sa),
+                "bound": "mfma", "achieved": achieved, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
+                "frac": achieved / INT8_MFMA_PEAK_TOPS,
+                "avg_launch_ms": gemm_ms / len(lin), "ops_per_launch": gemm_ops / len(lin),
+                "traffic": traffic}
+    by = opcount.block_algorithmic_bytes(D, H, N, hidden, sa, 4 if bw == 3 else bw)
+    alg_bytes = B * (by["per_image"] + N * D * 4) + by["weights"]     # + fp32 tokens read by vq_quantize
+    out = {
+        "metric": METRIC, "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "%s (ViT-B block, D=%d, H=%d, N=%d, hidden=%d), batch %d, W%dA%d, %s weights"
+                   % (name, D, H, N, hidden, B, bw, ba, "sharp-attention" if args.sharp else "as-stated"),
+                   "global_batch": B, "tokens": N, "parallelism": "single GPU"},
+        "images_per_s": ips,
+        "pct_of_int8_mfma_peak": 100.0 * tops / INT8_MFMA_PEAK_TOPS,
+        "hbm_algorithmic_gbs": alg_bytes / (dt / K) / 1e9,
+        "pct_of_hbm_peak_algorithmic": 100.0 * alg_bytes / (dt / K) / 1e9 / HBM_PEAK_GBS,
+        "stage_ms": stage_ms,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(name, args.sharp, bw, ba, ops_img)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

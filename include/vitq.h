@@ -159,6 +159,10 @@ typedef struct vq_block_desc {
     void *dump_o;     /* packed [B*N][D*storage_a/8]                                         */
     void *dump_x2;    /* packed [B*N][D*storage_a/8]        (hidden > 0 only)                */
     void *dump_h;     /* packed [B*N][hidden*storage_a/8]   (hidden > 0 only)                */
+    /* Optional profiling hook (host array of hipEvent_t, nullable): event 0 is recorded on the
+     * stream before the first stage and event i after stage i (1 QKV linear, 2 attention,
+     * 3 projection, 4 fc1, 5 fc2); 4 events are used when hidden == 0, else 6.              */
+    void **stage_events;
 } vq_block_desc;
 
 /* Bytes of workspace vq_attention_block needs for batch B (host computation only). */

@@ -349,6 +349,12 @@ vq_status vq_attention_block(const vq_block_desc *d, const vq_qmat *xq, int64_t 
     const int64_t BHN = B * d->H * d->N;
     const int64_t hrow = 64 * L.sa / 8;
 
+    int ev = 0;
+    auto mark = [&]() {
+        if (d->stage_events) (void)hipEventRecord((hipEvent_t)d->stage_events[ev], stream);
+        ++ev;
+    };
+    mark();
     // 1. QKV linear; the epilogue requantizes Q, K, V with their own steps, head-major
     LinearExtra ex;
     ex.head_major = 1; ex.D = d->D; ex.dh = 64; ex.Ntok = d->N; ex.Bimg = (int)B; ex.Hh = d->H;
@@ -356,6 +362,7 @@ vq_status vq_attention_block(const vq_block_desc *d, const vq_qmat *xq, int64_t 
     st = run_linear(xq, d->s_x, &d->w_qkv, d->sw_qkv, 1, d->b_qkv, 0, nullptr, nullptr, 0.0f, nullptr, &ex,
                     stream);
     if (st != VQ_OK) return st;
+    mark();
 
     // 2. fused attention: scores and P never leave the chip
     vq_qmat oq{};
@@ -376,17 +383,22 @@ vq_status vq_attention_block(const vq_block_desc *d, const vq_qmat *xq, int64_t 
         p.qsplit = pick_qsplit((int64_t)B * d->H, d->N);
         if (attention_launch(p, kAttnFused, stream) != hipSuccess) return VQ_ERR_HIP;
     }
+    mark();
 
     // 3. projection (fp32 out, or requantized for the MLP)
-    if (!d->hidden)
-        return run_linear(&oq, d->s_o, &d->w_proj, d->sw_proj, 1, d->b_proj, 0, nullptr, y_out, 0.0f, nullptr,
-                          nullptr, stream);
+    if (!d->hidden) {
+        st = run_linear(&oq, d->s_o, &d->w_proj, d->sw_proj, 1, d->b_proj, 0, nullptr, y_out, 0.0f, nullptr,
+                        nullptr, stream);
+        mark();
+        return st;
+    }
     vq_qmat x2{};
     x2.data = x2buf; x2.bits = d->bits_a; x2.storage_bits = L.sa; x2.rows = L.M; x2.cols = d->D;
     x2.row_stride = L.act_row;
     st = run_linear(&oq, d->s_o, &d->w_proj, d->sw_proj, 1, d->b_proj, 0, nullptr, nullptr, d->s_x2, &x2, nullptr,
                     stream);
     if (st != VQ_OK) return st;
+    mark();
     // 4. fc1 + GELU + requant, 5. fc2
     vq_qmat hq{};
     hq.data = hbuf; hq.bits = d->bits_a; hq.storage_bits = L.sa; hq.rows = L.M; hq.cols = d->hidden;
@@ -394,8 +406,11 @@ vq_status vq_attention_block(const vq_block_desc *d, const vq_qmat *xq, int64_t 
     st = run_linear(&x2, d->s_x2, &d->w_fc1, d->sw_fc1, 1, d->b_fc1, 1, nullptr, nullptr, d->s_h, &hq, nullptr,
                     stream);
     if (st != VQ_OK) return st;
-    return run_linear(&hq, d->s_h, &d->w_fc2, d->sw_fc2, 1, d->b_fc2, 0, nullptr, y_out, 0.0f, nullptr, nullptr,
-                      stream);
+    mark();
+    st = run_linear(&hq, d->s_h, &d->w_fc2, d->sw_fc2, 1, d->b_fc2, 0, nullptr, y_out, 0.0f, nullptr, nullptr,
+                    stream);
+    mark();
+    return st;
 }
 
 }  // extern "C"

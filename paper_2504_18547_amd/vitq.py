@@ -44,7 +44,7 @@ class vq_block_desc(C.Structure):
                 ("s_x", C.c_float), ("s_q", C.c_float), ("s_k", C.c_float), ("s_v", C.c_float),
                 ("s_o", C.c_float), ("s_x2", C.c_float), ("s_h", C.c_float), ("scale", C.c_float),
                 ("dump_qkv", C.c_void_p), ("dump_o", C.c_void_p), ("dump_x2", C.c_void_p),
-                ("dump_h", C.c_void_p)]
+                ("dump_h", C.c_void_p), ("stage_events", C.POINTER(C.c_void_p))]
 
 
 _lib = None

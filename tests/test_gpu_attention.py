@@ -40,18 +40,18 @@ def _check_qk(q, k, s_q, s_k, bits, bits_p, p_storage=None):
 def test_qk_4bit(B, H, N):
     rng = np.random.default_rng(B * 100 + H * 10 + N)
     q, k, _ = _heads(rng, B, H, N, 4)
-    ref = _check_qk(q, k, np.float32(0.41), np.float32(0.37), 4, 4)
+    ref = _check_qk(q, k, np.float32(0.62), np.float32(0.58), 4, 4)
     if N >= 37:
-        assert ref["p"].max() >= 8 and (ref["p"] > 0).mean() > 0.01       # not degenerate
+        assert ref["p"].max() >= 5 and (ref["p"] > 0).mean() > 0.003     # not degenerate
 
 
 @pytest.mark.parametrize("N", [197, 40, 577])
 def test_qk_8bit_operands_and_8bit_levels(N):
     rng = np.random.default_rng(900 + N)
     q, k, _ = _heads(rng, 1, 2, N, 8)
-    ref = _check_qk(q, k, np.float32(0.025), np.float32(0.022), 8, 8)
+    ref = _check_qk(q, k, np.float32(0.036), np.float32(0.034), 8, 8)
     assert ref["p"].max() > 100
-    _check_qk(q, k, np.float32(0.025), np.float32(0.022), 8, 4, p_storage=8)
+    _check_qk(q, k, np.float32(0.036), np.float32(0.034), 8, 4, p_storage=8)
 
 
 def test_qk_extremes_ties_and_uniform_rows():
