@@ -17,11 +17,14 @@ struct GemmParams {
     int32_t *acc_out; float *y_out; int vec_ok;      // vec_ok: Nout % 4 == 0 (aligned rows)
     uint8_t *yq; int64_t yq_stride; int yq_sb; int yq_row_bytes16;
     float s_y[3]; float qminf, qmaxf;
+    // constants of the guarded fast requantization (see gemm.hip): 1/s_y, the guard widths
+    float r_y[3]; float eps0; float gelu_guard;
     // head-major output of the QKV linear: channel -> (q/k/v, head, d), token -> (image, n)
     int head_major; int D, dh, Ntok, Bimg, Hh;
 };
 
 // wb / ab: storage bits of the weight / activation operand.  Supported: (4,4) (2,4) (8,8).
-hipError_t gemm_launch(const GemmParams &p, int wb, int ab, hipStream_t stream);
+// Fills the fast-path constants of p itself.
+hipError_t gemm_launch(GemmParams p, int wb, int ab, hipStream_t stream);
 
 }  // namespace vitq

@@ -5,13 +5,19 @@
 //
 // Both operands stay PACKED (b-bit fields) in HBM and in LDS; a lane unpacks its fragment to
 // int8 in registers right before the MFMA (2^(8-b)-scaled values, see vitq_dev.h), and the
-// epilogue removes the scale with an exact arithmetic shift.
+// epilogue removes the scale exactly.
 //
 // MFMA roles: the A operand (32 rows) carries WEIGHT rows (output channels), the B operand
 // (32 columns) carries TOKEN rows, so a lane of the 32x32 result holds 16 output channels of
 // ONE token.  Weight rows are placed in LDS in a permuted slot order so that those 16 channels
 // are consecutive: the lane then packs them into one 8-byte (4-bit) store of the token's
 // output row, which is exactly the packed operand layout the next linear reads.
+//
+// Epilogues.  The definition of a requantized output is level = clamp(rint(y / s)) with an IEEE
+// division.  The throughput epilogues evaluate a cheaper expression (multiplication by 1/s,
+// hardware exp2/rcp inside GELU) whose distance from the definition is bounded; an element
+// whose cheap value lies within that bound of a rounding boundary is recomputed with the exact
+// operation sequence.  The result is therefore always the definition's, bit for bit.
 #include "gemm.h"
 #include "vitq_dev.h"
 
@@ -19,7 +25,7 @@ namespace vitq {
 
 namespace {
 
-constexpr int kBK = 128;  // contraction values staged per LDS buffer
+enum Epi { kEpiGeneric = 0, kEpiF32 = 1, kEpiQuant = 2, kEpiQuantGelu = 3 };
 
 // channel c (0..31 within a 32-block) -> MFMA row slot, chosen so that a lane's sixteen
 // accumulator registers (rows 8*(r/4) + 4*(lane/32) + r%4) are channels 16*(lane/32) + r
@@ -45,10 +51,28 @@ __device__ __forceinline__ void store_packed16(uint8_t *dst, const int (&q)[16])
     }
 }
 
-// Epilogue for one 32x32 accumulator block: this lane owns token m and channels cb..cb+15.
-__device__ __forceinline__ void epilogue_block(const GemmParams &p, const v16i &acc, int shift,
-                                               int m, int cb, const float (&sc)[16],
-                                               const float (&bs)[16]) {
+// Destination of this lane's 16 packed levels; nullptr if nothing is to be stored.
+__device__ __forceinline__ uint8_t *packed_dst(const GemmParams &p, int m, int cb, int &which) {
+    which = 0;
+    if (p.head_major) {
+        if (cb >= p.Nout) return nullptr;
+        // channel -> (q/k/v, head, d); token -> (image, n)
+        which = cb / p.D;
+        int rem = cb - which * p.D;
+        int h = rem / p.dh;
+        int d = rem - h * p.dh;
+        int b = m / p.Ntok;
+        int n = m - b * p.Ntok;
+        int64_t row = (((int64_t)which * p.Bimg + b) * p.Hh + h) * p.Ntok + n;
+        return p.yq + row * p.yq_stride + ((d * p.yq_sb) >> 3);
+    }
+    if (((cb * p.yq_sb) >> 3) >= p.yq_row_bytes16) return nullptr;
+    return p.yq + (int64_t)m * p.yq_stride + ((cb * p.yq_sb) >> 3);
+}
+
+// ---- exact epilogue: every output kind, the definition's operation sequence ------------------
+__device__ __forceinline__ void epilogue_generic(const GemmParams &p, const v16i &acc, int shift,
+                                                 int m, int cb) {
     if (m >= p.M) return;
     const int nvalid = p.Nout - cb;  // may be <= 0 for a group that only exists as padding
     const bool full = nvalid >= 16;
@@ -56,8 +80,12 @@ __device__ __forceinline__ void epilogue_block(const GemmParams &p, const v16i &
     int a[16];
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
+        const int c = cb + r;
+        const bool ok = c < p.Nout;
+        const float sc = p.s_x * (ok ? p.s_w[p.s_w_per_channel ? c : 0] : 1.0f);
+        const float bsr = (ok && p.bias) ? p.bias[c] : 0.0f;
         a[r] = acc[r] >> shift;
-        float v = fmaf((float)a[r], sc[r], bs[r]);
+        float v = fmaf((float)a[r], sc, bsr);
         if (p.act == 1) v = gelu_tanh(v);
         y[r] = v;
     }
@@ -87,24 +115,11 @@ __device__ __forceinline__ void epilogue_block(const GemmParams &p, const v16i &
         }
     }
     if (p.yq) {
-        float s_y = p.s_y[0];
-        uint8_t *dst;
-        if (p.head_major) {
-            if (nvalid <= 0) return;
-            // channel -> (q/k/v, head, d); token -> (image, n)
-            int which = cb / p.D;
-            int rem = cb - which * p.D;
-            int h = rem / p.dh;
-            int d = rem - h * p.dh;
-            int b = m / p.Ntok;
-            int n = m - b * p.Ntok;
-            s_y = which == 0 ? p.s_y[0] : (which == 1 ? p.s_y[1] : p.s_y[2]);
-            int64_t row = (((int64_t)which * p.Bimg + b) * p.Hh + h) * p.Ntok + n;
-            dst = p.yq + row * p.yq_stride + ((d * p.yq_sb) >> 3);
-        } else {
-            if (((cb * p.yq_sb) >> 3) >= p.yq_row_bytes16) return;
-            dst = p.yq + (int64_t)m * p.yq_stride + ((cb * p.yq_sb) >> 3);
-        }
+        int which;
+        uint8_t *dst = packed_dst(p, m, cb, which);
+        if (!dst) return;
+        const float sy0 = p.s_y[0], sy1 = p.s_y[1], sy2 = p.s_y[2];
+        const float s_y = which == 0 ? sy0 : (which == 1 ? sy1 : sy2);
         int q[16];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -117,22 +132,139 @@ __device__ __forceinline__ void epilogue_block(const GemmParams &p, const v16i &
     }
 }
 
-template <int WB, int AB, int TC, int TT, int WAVES_C, int WAVES_T>
-__global__ __launch_bounds__(WAVES_C *WAVES_T * 64) void gemm_kernel(GemmParams p) {
+// ---- fp32-only epilogue (Nout % 16 == 0, aligned): convert, one fma, store --------------------
+// scs = sc * 2^-shift exactly, so fma((float)acc_scaled, scs, b) == fma((float)acc, sc, b).
+__device__ __forceinline__ void epilogue_f32(const GemmParams &p, const v16i &acc, int shift, int m, int cb,
+                                             const float (&scs)[16], const float (&bs)[16], bool fold_ok) {
+    if (m >= p.M || cb >= p.Nout) return;
+    if (!fold_ok) {   // subnormal-small scales: shift first, then the unfolded scale
+        float *out = p.y_out + (int64_t)m * p.Nout + cb;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float sc = p.s_x * p.s_w[p.s_w_per_channel ? cb + r : 0];
+            out[r] = fmaf((float)(acc[r] >> shift), sc, bs[r]);
+        }
+        return;
+    }
+    float4 *dst = reinterpret_cast<float4 *>(p.y_out + (int64_t)m * p.Nout + cb);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float4 v;
+        v.x = fmaf((float)acc[4 * j + 0], scs[4 * j + 0], bs[4 * j + 0]);
+        v.y = fmaf((float)acc[4 * j + 1], scs[4 * j + 1], bs[4 * j + 1]);
+        v.z = fmaf((float)acc[4 * j + 2], scs[4 * j + 2], bs[4 * j + 2]);
+        v.w = fmaf((float)acc[4 * j + 3], scs[4 * j + 3], bs[4 * j + 3]);
+        dst[j] = v;
+    }
+}
+
+// ---- guarded fast requantization (Nout % 16 == 0; 4- or 8-bit storage) ------------------------
+// Cheap value: t8 = fma(y, 1/s, -qmin) ~ y/s - qmin, level+(-qmin) = rint(t8).  With T = y/s:
+//   |t8 + qmin - fl(T)| <= |T| * 2^-23 + ulp(t8)/2  <  eps0 = 2^(bits-22)   whenever |T| <= qmax+2,
+// and beyond that range both values clamp to the same level.  If rint(t8) is not within
+// 1/2 - eps0 of t8, the definition rounds to the same integer; otherwise the element is redone
+// exactly.  For GELU the cheap activation (hardware exp2 / rcp) is within
+// 2^-18 * |y| * max(1,|y|) of the definition's, which widens the guard per element.
+template <bool GELU>
+__device__ __forceinline__ void epilogue_quant(const GemmParams &p, const v16i &acc, int shift, int m,
+                                               int cb, const float (&scs)[16], const float (&bs)[16],
+                                               bool force_exact) {
+    if (m >= p.M) return;
+    int which;
+    uint8_t *dst = packed_dst(p, m, cb, which);
+    if (!dst) return;
+    const float sy0 = p.s_y[0], sy1 = p.s_y[1], sy2 = p.s_y[2];
+    const float ry0 = p.r_y[0], ry1 = p.r_y[1], ry2 = p.r_y[2];
+    const float s_y = which == 0 ? sy0 : (which == 1 ? sy1 : sy2);
+    const float r_y = which == 0 ? ry0 : (which == 1 ? ry1 : ry2);
+    const float bias8 = -p.qminf;
+    const float top = p.qmaxf - p.qminf;
+    const float thr0 = 0.5f - p.eps0;
+    const float gguard = p.gelu_guard * r_y;
+    float lv[16];
+    bool risky = force_exact;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const float y = fmaf((float)acc[r], scs[r], bs[r]);        // the definition's y, exactly
+        float g = y, thr = thr0;
+        if constexpr (GELU) {
+            // 0.5*y*(1+tanh(u)) = y - y/(1 + 2^(2u*log2 e)),  2u*log2e = y*(k0 + k1*y^2)
+            const float y2 = y * y;
+            const float w = fmaf(y2, 0x1.a5a7d0p-4f, 0x1.26aec2p+1f);
+            const float X = __builtin_amdgcn_exp2f(w * y);
+            const float rc = __builtin_amdgcn_rcpf(1.0f + X);
+            g = fmaf(-y, rc, y);
+            const float ay = fabsf(y);
+            thr = fmaf(-(ay * fmaxf(ay, 1.0f)), gguard, thr0);
+        }
+        const float t8 = fmaf(g, r_y, bias8);
+        const float q8 = rintf(t8);
+        risky = risky || (fabsf(t8 - q8) > thr);
+        lv[r] = __builtin_amdgcn_fmed3f(q8, 0.0f, top);
+    }
+    if (__builtin_amdgcn_ballot_w64(risky) != 0) {
+        // some element of this wave's 32x32 block sits within the error bound of a rounding
+        // boundary: redo the block with the definition's exact operation sequence (rare)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            // (re-read the channel's step: the folded copy may be inexact when force_exact is set)
+            const float sc = p.s_x * p.s_w[p.s_w_per_channel ? cb + r : 0];
+            float ye = fmaf((float)(acc[r] >> shift), sc, bs[r]);
+            if constexpr (GELU) ye = gelu_tanh(ye);
+            const float te = rintf(ye / s_y) + bias8;
+            lv[r] = __builtin_amdgcn_fmed3f(te, 0.0f, top);
+        }
+    }
+    if (p.yq_sb == 4) {
+        // even-indexed levels in the low nibbles of one word, odd-indexed shifted into the high
+        u32 ev0 = 0, od0 = 0, ev1 = 0, od1 = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            ev0 = __builtin_amdgcn_cvt_pk_u8_f32(lv[2 * i], i, ev0);
+            od0 = __builtin_amdgcn_cvt_pk_u8_f32(lv[2 * i + 1], i, od0);
+            ev1 = __builtin_amdgcn_cvt_pk_u8_f32(lv[8 + 2 * i], i, ev1);
+            od1 = __builtin_amdgcn_cvt_pk_u8_f32(lv[8 + 2 * i + 1], i, od1);
+        }
+        // stored levels are biased by -qmin = 8; flipping bit 3 turns them into two's complement
+        const u32 w0 = (ev0 | (od0 << 4)) ^ 0x88888888u;
+        const u32 w1 = (ev1 | (od1 << 4)) ^ 0x88888888u;
+        *reinterpret_cast<uint2 *>(dst) = make_uint2(w0, w1);
+    } else {
+        // 8-bit storage: the bias -qmin = 2^(bits-1) is removed modulo 256
+        const u32 fix = 0x01010101u * ((u32)bias8 & 0xFFu);
+        u32 w[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            u32 v = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v = __builtin_amdgcn_cvt_pk_u8_f32(lv[4 * j + i], i, v);
+            // per-byte subtraction of the bias: (v - fix) without borrows across bytes
+            w[j] = ((v | 0x80808080u) - (fix & 0x7F7F7F7Fu)) ^ ((v ^ ~fix) & 0x80808080u);
+        }
+        *reinterpret_cast<uint4 *>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
+template <int WB, int AB, int TC, int TT, int WAVES_C, int WAVES_T, int BK, int EPI>
+__global__ __launch_bounds__(WAVES_C *WAVES_T * 64, ((TC / WAVES_C) * (TT / WAVES_T) <= 8192 ? 2 : 1))
+void gemm_kernel(GemmParams p) {
     constexpr int NT = WAVES_C * WAVES_T * 64;
-    constexpr int WROW = kBK * WB / 8, XROW = kBK * AB / 8;   // bytes per row per stage
+    constexpr int WROW = BK * WB / 8, XROW = BK * AB / 8;     // bytes per row per stage
     constexpr int WPITCH = WROW + 16, XPITCH = XROW + 16;     // LDS row pitch (bank spread)
     constexpr int WCH = WROW / 16, XCH = XROW / 16;           // 16-byte chunks per row
     constexpr int W_ITERS = TC * WCH / NT, X_ITERS = TT * XCH / NT;
     static_assert((TC * WCH) % NT == 0 && (TT * XCH) % NT == 0, "tile/threads mismatch");
     constexpr int WC = TC / WAVES_C, WT = TT / WAVES_T;       // wave tile
     constexpr int NC = WC / 32, NTK = WT / 32;                // 32x32 blocks per wave
-    static_assert(WC % 32 == 0 && WT % 32 == 0 && TC % 64 == 0, "wave tile");
+    static_assert(WC % 32 == 0 && WT % 32 == 0 && TC % 64 == 0 && BK % 64 == 0, "wave tile");
     constexpr int WBUF = TC * WPITCH, XBUF = TT * XPITCH;
 
-    __shared__ __attribute__((aligned(16))) uint8_t smem[2 * (WBUF + XBUF)];
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     uint8_t *sW = smem;
     uint8_t *sX = smem + 2 * WBUF;
+    float *s_scs = reinterpret_cast<float *>(smem + 2 * (WBUF + XBUF));   // [TC] folded scales
+    float *s_bs = s_scs + TC;                                             // [TC] biases
+    int *s_fold_bad = reinterpret_cast<int *>(s_bs + TC);                 // [1] flag
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -142,11 +274,40 @@ __global__ __launch_bounds__(WAVES_C *WAVES_T * 64) void gemm_kernel(GemmParams 
     const int li = lane & 31;   // MFMA row / column index of this lane
     const int g = lane >> 5;    // k-group of this lane
 
+    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Re-number them so
+    // that the workgroups of one XCD walk consecutive tiles: the channel tiles of one token tile
+    // then share that XCD's L2 copy of the activations.
     const int n_ct = (p.Nout + TC - 1) / TC;
-    const int ct = blockIdx.x % n_ct;
-    const int tt = blockIdx.x / n_ct;
+    int logical;
+    {
+        const int total = gridDim.x, id = blockIdx.x;
+        const int xcd = id & 7, slot = id >> 3;
+        const int per = total >> 3, rem = total & 7;
+        logical = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + slot;
+    }
+    const int ct = logical % n_ct;
+    const int tt = logical / n_ct;
     const int c0 = ct * TC;
     const int t0 = tt * TT;
+
+    // Per-channel epilogue constants, staged once per tile while the first operand loads are in
+    // flight: sc = s_x*s_w[c] (the definition's exact product) with the operand factor 2^shift
+    // folded in.  The fold is exact unless the result is subnormal; a flag then sends the whole
+    // tile through the exact operation sequence.
+    if constexpr (EPI != kEpiGeneric) {
+        if (tid == 0) s_fold_bad[0] = 0;
+        __syncthreads();
+        for (int c = tid; c < TC; c += NT) {
+            const int ch = c0 + c;
+            const bool ok = ch < p.Nout;
+            const float sw = ok ? p.s_w[p.s_w_per_channel ? ch : 0] : 1.0f;
+            const float sc = p.s_x * sw;
+            const float folded = ldexpf(sc, -Shift<WB, AB>::value);
+            s_scs[c] = folded;
+            s_bs[c] = (ok && p.bias) ? p.bias[ch] : 0.0f;
+            if (!(ldexpf(folded, Shift<WB, AB>::value) == sc)) s_fold_bad[0] = 1;
+        }
+    }
 
     v16i acc[NC][NTK];
 #pragma unroll
@@ -201,23 +362,25 @@ __global__ __launch_bounds__(WAVES_C *WAVES_T * 64) void gemm_kernel(GemmParams 
         const uint8_t *bw = sW + buf * WBUF + (wave_c * WC + li) * WPITCH;
         const uint8_t *bx = sX + buf * XBUF + (wave_t * WT + li) * XPITCH;
 #pragma unroll
-        for (int ss = 0; ss < kBK / 64; ++ss) {
-            // lane g owns values [64*ss + 32*g, +32): two MFMA operands of 16 values each
-            v4i wf[NC][2], xf[NTK][2];
+        for (int ss = 0; ss < BK / 64; ++ss) {
+            // lane g owns values [64*ss + 32*g, +32): two MFMA operands of 16 values each,
+            // fetched packed with one LDS read and unpacked one operand at a time
+            constexpr int WRAW = (32 * WB) / 32, XRAW = (32 * AB) / 32;   // dwords per lane
+            u32 wr[NC][WRAW], xr[NTK][XRAW];
 #pragma unroll
             for (int ci = 0; ci < NC; ++ci) {
                 const uint8_t *src = bw + ci * 32 * WPITCH + ((ss * 64 + g * 32) * WB) / 8;
                 if constexpr (WB == 4) {
                     uint4 v = *reinterpret_cast<const uint4 *>(src);
-                    wf[ci][0] = unpack4_x16(v.x, v.y);
-                    wf[ci][1] = unpack4_x16(v.z, v.w);
+                    wr[ci][0] = v.x; wr[ci][1] = v.y; wr[ci][2] = v.z; wr[ci][3] = v.w;
                 } else if constexpr (WB == 2) {
                     uint2 v = *reinterpret_cast<const uint2 *>(src);
-                    wf[ci][0] = unpack2_x64(v.x);
-                    wf[ci][1] = unpack2_x64(v.y);
+                    wr[ci][0] = v.x; wr[ci][1] = v.y;
                 } else {
-                    wf[ci][0] = *reinterpret_cast<const v4i *>(src);
-                    wf[ci][1] = *reinterpret_cast<const v4i *>(src + 16);
+                    uint4 v0 = *reinterpret_cast<const uint4 *>(src);
+                    uint4 v1 = *reinterpret_cast<const uint4 *>(src + 16);
+                    wr[ci][0] = v0.x; wr[ci][1] = v0.y; wr[ci][2] = v0.z; wr[ci][3] = v0.w;
+                    wr[ci][4] = v1.x; wr[ci][5] = v1.y; wr[ci][6] = v1.z; wr[ci][7] = v1.w;
                 }
             }
 #pragma unroll
@@ -225,30 +388,44 @@ __global__ __launch_bounds__(WAVES_C *WAVES_T * 64) void gemm_kernel(GemmParams 
                 const uint8_t *src = bx + ti * 32 * XPITCH + ((ss * 64 + g * 32) * AB) / 8;
                 if constexpr (AB == 4) {
                     uint4 v = *reinterpret_cast<const uint4 *>(src);
-                    if constexpr (WB == 2) {
-                        xf[ti][0] = unpack4_x16_order2(v.x, v.y);
-                        xf[ti][1] = unpack4_x16_order2(v.z, v.w);
-                    } else {
-                        xf[ti][0] = unpack4_x16(v.x, v.y);
-                        xf[ti][1] = unpack4_x16(v.z, v.w);
-                    }
+                    xr[ti][0] = v.x; xr[ti][1] = v.y; xr[ti][2] = v.z; xr[ti][3] = v.w;
                 } else {
-                    xf[ti][0] = *reinterpret_cast<const v4i *>(src);
-                    xf[ti][1] = *reinterpret_cast<const v4i *>(src + 16);
+                    uint4 v0 = *reinterpret_cast<const uint4 *>(src);
+                    uint4 v1 = *reinterpret_cast<const uint4 *>(src + 16);
+                    xr[ti][0] = v0.x; xr[ti][1] = v0.y; xr[ti][2] = v0.z; xr[ti][3] = v0.w;
+                    xr[ti][4] = v1.x; xr[ti][5] = v1.y; xr[ti][6] = v1.z; xr[ti][7] = v1.w;
                 }
             }
 #pragma unroll
-            for (int s = 0; s < 2; ++s)
+            for (int s = 0; s < 2; ++s) {
+                v4i wf[NC], xf[NTK];
+#pragma unroll
+                for (int ci = 0; ci < NC; ++ci) {
+                    if constexpr (WB == 4) wf[ci] = unpack4_x16(wr[ci][2 * s], wr[ci][2 * s + 1]);
+                    else if constexpr (WB == 2) wf[ci] = unpack2_x64(wr[ci][s]);
+                    else { wf[ci][0] = (int)wr[ci][4 * s]; wf[ci][1] = (int)wr[ci][4 * s + 1];
+                           wf[ci][2] = (int)wr[ci][4 * s + 2]; wf[ci][3] = (int)wr[ci][4 * s + 3]; }
+                }
+#pragma unroll
+                for (int ti = 0; ti < NTK; ++ti) {
+                    if constexpr (AB == 4) {
+                        if constexpr (WB == 2) xf[ti] = unpack4_x16_order2(xr[ti][2 * s], xr[ti][2 * s + 1]);
+                        else xf[ti] = unpack4_x16(xr[ti][2 * s], xr[ti][2 * s + 1]);
+                    } else {
+                        xf[ti][0] = (int)xr[ti][4 * s]; xf[ti][1] = (int)xr[ti][4 * s + 1];
+                        xf[ti][2] = (int)xr[ti][4 * s + 2]; xf[ti][3] = (int)xr[ti][4 * s + 3];
+                    }
+                }
 #pragma unroll
                 for (int ci = 0; ci < NC; ++ci)
 #pragma unroll
                     for (int ti = 0; ti < NTK; ++ti)
-                        acc[ci][ti] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[ci][s], xf[ti][s],
-                                                                            acc[ci][ti], 0, 0, 0);
+                        acc[ci][ti] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[ci], xf[ti], acc[ci][ti], 0, 0, 0);
+            }
         }
     };
 
-    const int nk = (p.K + kBK - 1) / kBK;
+    const int nk = (p.K + BK - 1) / BK;
     gload(0);
     sstore(0);
     __syncthreads();
@@ -262,42 +439,80 @@ __global__ __launch_bounds__(WAVES_C *WAVES_T * 64) void gemm_kernel(GemmParams 
 
     // ---- epilogue -------------------------------------------------------------------------
     constexpr int shift = Shift<WB, AB>::value;
+    const bool fold_ok = (EPI != kEpiGeneric) && (s_fold_bad[0] == 0);
+    static_for<NC>([&](auto CI) {
+        constexpr int ci = decltype(CI)::value;
+        const int cl = wave_c * WC + ci * 32 + 16 * g;     // channel offset inside the tile
+        const int cb = c0 + cl;
+        float bs[16], scs[16];
+        if constexpr (EPI != kEpiGeneric) {
 #pragma unroll
-    for (int ci = 0; ci < NC; ++ci) {
-        const int cb = c0 + wave_c * WC + ci * 32 + 16 * g;
-        float sc[16], bs[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            int c = cb + r;
-            bool ok = c < p.Nout;
-            float sw = ok ? p.s_w[p.s_w_per_channel ? c : 0] : 1.0f;
-            sc[r] = p.s_x * sw;
-            bs[r] = (ok && p.bias) ? p.bias[c] : 0.0f;
+            for (int j = 0; j < 4; ++j) {
+                const float4 a = *reinterpret_cast<const float4 *>(s_scs + cl + 4 * j);
+                const float4 b = *reinterpret_cast<const float4 *>(s_bs + cl + 4 * j);
+                scs[4 * j] = a.x; scs[4 * j + 1] = a.y; scs[4 * j + 2] = a.z; scs[4 * j + 3] = a.w;
+                bs[4 * j] = b.x; bs[4 * j + 1] = b.y; bs[4 * j + 2] = b.z; bs[4 * j + 3] = b.w;
+            }
         }
-#pragma unroll
-        for (int ti = 0; ti < NTK; ++ti) {
+        static_for<NTK>([&](auto TI) {
+            constexpr int ti = decltype(TI)::value;
             const int m = t0 + wave_t * WT + ti * 32 + li;
-            epilogue_block(p, acc[ci][ti], shift, m, cb, sc, bs);
-        }
-    }
+            if constexpr (EPI == kEpiF32) epilogue_f32(p, acc[ci][ti], shift, m, cb, scs, bs, fold_ok);
+            else if constexpr (EPI == kEpiQuant) epilogue_quant<false>(p, acc[ci][ti], shift, m, cb, scs, bs, !fold_ok);
+            else if constexpr (EPI == kEpiQuantGelu) epilogue_quant<true>(p, acc[ci][ti], shift, m, cb, scs, bs, !fold_ok);
+            else epilogue_generic(p, acc[ci][ti], shift, m, cb);
+        });
+    });
 }
 
-template <int WB, int AB, int TC, int TT, int WAVES_C, int WAVES_T>
+template <int WB, int AB, int TC, int TT, int WAVES_C, int WAVES_T, int BK, int EPI>
 hipError_t launch(const GemmParams &p, hipStream_t stream) {
+    constexpr int WPITCH = BK * WB / 8 + 16, XPITCH = BK * AB / 8 + 16;
+    constexpr size_t lds = 2 * ((size_t)TC * WPITCH + (size_t)TT * XPITCH) + 2 * TC * sizeof(float) + 16;
+    auto kern = gemm_kernel<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, EPI>;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
     const int n_ct = (p.Nout + TC - 1) / TC;
     const int n_tt = (p.M + TT - 1) / TT;
     const int64_t blocks = (int64_t)n_ct * n_tt;
-    hipLaunchKernelGGL((gemm_kernel<WB, AB, TC, TT, WAVES_C, WAVES_T>), dim3((unsigned)blocks),
-                       dim3(WAVES_C * WAVES_T * 64), 0, stream, p);
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(WAVES_C * WAVES_T * 64), lds, stream, p);
     return hipGetLastError();
+}
+
+template <int WB, int AB, int TC, int TT, int WAVES_C, int WAVES_T, int BK>
+hipError_t launch_epi(const GemmParams &p, int epi, hipStream_t stream) {
+    switch (epi) {
+        case kEpiF32: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, kEpiF32>(p, stream);
+        case kEpiQuant: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, kEpiQuant>(p, stream);
+        case kEpiQuantGelu: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, kEpiQuantGelu>(p, stream);
+        default: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, kEpiGeneric>(p, stream);
+    }
 }
 
 }  // namespace
 
-hipError_t gemm_launch(const GemmParams &p, int wb, int ab, hipStream_t stream) {
-    if (wb == 4 && ab == 4) return launch<4, 4, 128, 128, 2, 2>(p, stream);
-    if (wb == 2 && ab == 4) return launch<2, 4, 128, 128, 2, 2>(p, stream);
-    if (wb == 8 && ab == 8) return launch<8, 8, 128, 128, 2, 2>(p, stream);
+hipError_t gemm_launch(GemmParams p, int wb, int ab, hipStream_t stream) {
+    // pick the epilogue: the specialised ones need full 16-channel groups and a single output
+    int epi = kEpiGeneric;
+    const bool aligned = (p.Nout % 16 == 0);
+    if (aligned && !p.acc_out) {
+        if (p.y_out && !p.yq && p.act == 0 && p.vec_ok) epi = kEpiF32;
+        if (p.yq && !p.y_out && (p.yq_sb == 4 || p.yq_sb == 8)) epi = p.act == 1 ? kEpiQuantGelu : kEpiQuant;
+    }
+    if (p.yq) {
+        for (int i = 0; i < 3; ++i) p.r_y[i] = 1.0f / p.s_y[i];
+        p.eps0 = ldexpf(1.0f, (p.qmaxf > 7.5f ? 8 : 4) - 22);
+        p.gelu_guard = ldexpf(1.0f, -18);
+        // a step so small that 1/s overflows, or so large that it underflows, takes the exact path
+        for (int i = 0; i < 3; ++i)
+            if (!(p.r_y[i] > 0x1p-100f && p.r_y[i] < 0x1p100f)) epi = (epi == kEpiF32) ? epi : kEpiGeneric;
+    }
+    if (wb == 4 && ab == 4) return launch_epi<4, 4, 128, 128, 2, 2, 128>(p, epi, stream);
+    if (wb == 2 && ab == 4) return launch_epi<2, 4, 128, 128, 2, 2, 128>(p, epi, stream);
+    if (wb == 8 && ab == 8) return launch_epi<8, 8, 128, 128, 2, 2, 128>(p, epi, stream);
     return hipErrorInvalidValue;
 }
 

@@ -7,6 +7,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <utility>
+
 namespace vitq {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
@@ -14,6 +16,17 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 typedef unsigned int u32;
 
 constexpr int kWave = 64;
+
+// Compile-time loop: the body receives std::integral_constant indices, so register arrays are
+// only ever indexed by constants (a run-time index would push them to scratch memory).
+template <int... I, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F &&f) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+    static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
 
 // ---------------------------------------------------------------------------------------
 // Uniform quantizer: clamp(round-half-even(y / s), qmin, qmax).  (Sec. IV-B / IV-C thresholds
