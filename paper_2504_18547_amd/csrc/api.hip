@@ -100,13 +100,23 @@ int pick_qsplit(int64_t heads, int N) {
 // alpha = ((s_q*s_k)*scale)*log2(e) in fp32, then divided by the 2^shift operand factor.
 // The division by a power of two must be exact for the kernel's product to round like the
 // definition's; it is unless alpha is subnormal-small.
-bool scaled_alpha(float s_q, float s_k, float scale, int shift, float *out) {
+bool scaled_alpha(float s_q, float s_k, float scale, int shift, AttnParams *p) {
     const float kLog2e = 0x1.715476p+0f;
     float alpha = ((s_q * s_k) * scale) * kLog2e;
     if (!good_step(alpha)) return false;
     float scaled = ldexpf(alpha, -shift);
     if (!(ldexpf(scaled, shift) == alpha) || !isnormal(scaled)) return false;
-    *out = scaled;
+    p->alpha_scaled = scaled;
+    p->alpha = alpha;
+    // Exponential table for 4-bit operands: the score difference d = max - S is an integer in
+    // [0, 8192].  Beyond alpha*d >= 22.5 the fixed-point value is 0 (the shift is >= 22 and the
+    // mantissa is < 2^22), so the table ends there with one shared zero entry.
+    p->lut_n = 0;
+    if (shift == 8) {
+        double need = 22.5 / (double)alpha + 2.0;
+        int n = need > 8193.0 ? 8193 : (int)need;
+        p->lut_n = n + 1;
+    }
     return true;
 }
 
@@ -204,7 +214,7 @@ vq_status vq_matmul_qk(const vq_qmat *q, const vq_qmat *k, int32_t B, int32_t H,
         p.p_out = (uint8_t *)p_out->data; p.p_out_stride = p_out->row_stride;
         p.p_out_row_bytes16 = (int)row_bytes16(p_out);
     }
-    if (!scaled_alpha(s_q, s_k, scale, q->storage_bits == 4 ? 8 : 0, &p.alpha_scaled)) return VQ_ERR_STEP;
+    if (!scaled_alpha(s_q, s_k, scale, q->storage_bits == 4 ? 8 : 0, &p)) return VQ_ERR_STEP;
     if (rows == 0) return VQ_OK;
     p.q = (const uint8_t *)q->data; p.k = (const uint8_t *)k->data;
     p.q_stride = q->row_stride; p.k_stride = k->row_stride; p.sb = q->storage_bits;
@@ -253,6 +263,7 @@ vq_status vq_matmul_pv(const vq_qmat *pm, const vq_qmat *v, int32_t B, int32_t H
     p.spv = s_p * s_v;
     p.o_acc_out = o_acc_out; p.o_out = o_out;
     p.qsplit = pick_qsplit((int64_t)B * H, N);
+    p.r_o = 1.0f / p.s_o; p.eps_o = ldexpf(1.0f, (p.qmaxf > 7.5f ? 8 : 4) - 22);
     hipError_t e = attention_launch(p, kAttnPVOnly, (hipStream_t)stream);
     return e == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }
@@ -331,8 +342,8 @@ vq_status vq_attention_block(const vq_block_desc *d, const vq_qmat *xq, int64_t 
     if (!good_step(d->s_x) || !good_step(d->s_q) || !good_step(d->s_k) || !good_step(d->s_v) ||
         !good_step(d->s_o) || !good_step(d->scale))
         return VQ_ERR_STEP;
-    float alpha_scaled;
-    if (!scaled_alpha(d->s_q, d->s_k, d->scale, L.sa == 4 ? 8 : 0, &alpha_scaled)) return VQ_ERR_STEP;
+    AttnParams ap{};
+    if (!scaled_alpha(d->s_q, d->s_k, d->scale, L.sa == 4 ? 8 : 0, &ap)) return VQ_ERR_STEP;
     if (B == 0) return VQ_OK;
     if (!y_out) return VQ_ERR_NULL;
     if (!workspace || workspace_bytes < L.total) return VQ_ERR_WORKSPACE;
@@ -369,11 +380,10 @@ vq_status vq_attention_block(const vq_block_desc *d, const vq_qmat *xq, int64_t 
     oq.data = obuf; oq.bits = d->bits_a; oq.storage_bits = L.sa; oq.rows = L.M; oq.cols = d->D;
     oq.row_stride = L.act_row;
     {
-        AttnParams p{};
+        AttnParams p = ap;
         p.q = qkv; p.k = qkv + BHN * hrow; p.v = qkv + 2 * BHN * hrow;
         p.q_stride = p.k_stride = p.v_stride = hrow;
         p.sb = L.sa; p.B = (int)B; p.H = d->H; p.N = d->N;
-        p.alpha_scaled = alpha_scaled;
         p.pmax = (1 << d->bits_p) - 1;
         p.p_sb = L.sa;
         p.spv = (1.0f / (float)p.pmax) * d->s_v;
@@ -381,6 +391,7 @@ vq_status vq_attention_block(const vq_block_desc *d, const vq_qmat *xq, int64_t 
         level_range(d->bits_a, &p.qminf, &p.qmaxf);
         p.oq = obuf; p.oq_stride = L.act_row; p.oq_sb = L.sa;
         p.qsplit = pick_qsplit((int64_t)B * d->H, d->N);
+        p.r_o = 1.0f / p.s_o; p.eps_o = ldexpf(1.0f, (p.qmaxf > 7.5f ? 8 : 4) - 22);
         if (attention_launch(p, kAttnFused, stream) != hipSuccess) return VQ_ERR_HIP;
     }
     mark();

@@ -16,6 +16,8 @@ struct AttnParams {
     int B, H, N;
     // softmax
     float alpha_scaled;          // ((s_q*s_k)*scale)*log2(e), divided by the operand scale 2^8 at 4 bits
+    float alpha;                 // the same, unscaled (fills the exponential table)
+    int lut_n;                   // entries of the exponential table (0: compute directly)
     int pmax;                    // 2^bits_p - 1
     // P as an input (PV-only) or output (QK-only), packed unsigned [B*H*N x N]
     const uint8_t *p_in; int64_t p_in_stride; int p_in_row_bytes16;
@@ -25,6 +27,7 @@ struct AttnParams {
     // output side of P.V
     float spv;                   // s_p * s_v
     float s_o, qminf, qmaxf;
+    float r_o, eps_o;            // 1/s_o and the guard width of the fast requantization
     int32_t *o_acc_out;          // [B*H*N x 64] or null
     float *o_out;                // [B*N x H*64] or null
     uint8_t *oq; int64_t oq_stride; int oq_sb;   // packed [B*N x H*64] or null

@@ -30,8 +30,20 @@ __device__ __forceinline__ int vt_pos(int n) {
     return (n & ~63) + (((n & 15) >> 2) << 4) + (((n & 63) >> 4) << 2) + (n & 3);
 }
 
-template <int NT, int SB, int MODE, bool P8>
-__global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
+// (1+r) << floor(alpha*d) in 12.20 fixed point for an integer score difference d <= 0 (Eq. 4)
+__device__ __forceinline__ u32 shift_exp_fixed(int d, float alpha) {
+    float tt = alpha * (float)d;
+    float f = floorf(tt);
+    float fr = tt - f;
+    u32 u = (u32)((1.0f + fr) * 1048576.0f);
+    float nf = -f;
+    int sh = (nf >= 31.0f) ? 31 : (int)nf;
+    return u >> sh;
+}
+
+// TAIL: N > 16*(NT-1), i.e. every key tile but the last holds only real keys (no masking there).
+template <int NT, int SB, int MODE, bool P8, bool LUT, bool TAIL>
+__global__ __launch_bounds__(256, (NT <= 13 ? 2 : 1)) void attention_kernel(AttnParams p) {
     constexpr int NCH = (NT + 3) / 4;                 // 64-key chunks of the P.V contraction
     constexpr int NKEYP = NCH * 64;                   // padded key count of V^T rows
     constexpr int KROW = 64 * SB / 8;                 // bytes of one packed K row
@@ -41,6 +53,8 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     uint8_t *sK = smem;                               // [NT*16][KPITCH]
     uint8_t *sVT = smem + ((NT * 16 * KPITCH + 15) & ~15);  // [64][VPITCH] int8
+    u32 *sLUT = reinterpret_cast<u32 *>(sVT + 64 * VPITCH);  // [lut_n] exponential table (4-bit)
+    const int lut_last = p.lut_n - 1;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -53,6 +67,12 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
     const int N = p.N;
     const int64_t row0 = (int64_t)bh * N;             // first row of this head in q/k/v/p
 
+    if constexpr (LUT && MODE != kAttnPVOnly) {
+        // entry d: the fixed-point exponential of score difference -d, by the exact operation
+        // sequence; the last entry stands for every larger difference, where the value is 0
+        for (int i = tid; i < p.lut_n; i += 256)
+            sLUT[i] = (i == lut_last) ? 0u : shift_exp_fixed(-i, p.alpha);
+    }
     // ---- stage K (packed) and V^T (int8) ---------------------------------------------------
     if constexpr (MODE != kAttnPVOnly) {
         constexpr int CH = KROW / 8;                  // 8-byte pieces per row
@@ -124,15 +144,19 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
                 v4i z = {0, 0, 0, 0};
                 s[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(kf, qf, z, 0, 0, 0);
             }
+            // Tiles t < n_full hold only real keys (known at compile time in the TAIL variant).
             // ---- integer row max (keys >= N excluded) ---------------------------------------
             int mx = INT32_MIN;
+            static_for<NT>([&](auto T) {
+                constexpr int t = decltype(T)::value;
+                if (TAIL && t < NT - 1) {
+                    mx = max(mx, max(max(s[t][0], s[t][1]), max(s[t][2], s[t][3])));
+                } else {
 #pragma unroll
-            for (int t = 0; t < NT; ++t)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int key = 16 * t + 4 * g + r;
-                    if (key < N) mx = max(mx, s[t][r]);
+                    for (int r = 0; r < 4; ++r)
+                        if (16 * t + 4 * g + r < N) mx = max(mx, s[t][r]);
                 }
+            });
             mx = max(mx, __shfl_xor(mx, 16, 64));
             mx = max(mx, __shfl_xor(mx, 32, 64));
             if constexpr (MODE == kAttnQKOnly) {
@@ -147,47 +171,75 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
                         }
                 }
             }
-            // ---- shift-based exponential in 12.20 fixed point, integer row sum --------------
-            u32 sum = 0;
-#pragma unroll
-            for (int t = 0; t < NT; ++t)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int key = 16 * t + 4 * g + r;
-                    u32 e = 0;
-                    if (key < N) {
-                        float tt = p.alpha_scaled * (float)(s[t][r] - mx);
-                        float f = floorf(tt);
-                        float fr = tt - f;
-                        u32 u = (u32)((1.0f + fr) * 1048576.0f);
-                        float nf = -f;
-                        int sh = (nf >= 31.0f) ? 31 : (int)nf;
-                        e = u >> sh;
-                    }
-                    s[t][r] = (int)e;
-                    sum += e;
+            // ---- shift-based exponential in 12.20 fixed point (Eq. 4), integer row sum -------
+            // e depends only on the integer difference d = max - S, so at 4 bits (d <= 8192) it is
+            // read from a table that this workgroup filled with the exact operation sequence.
+            auto exp_of = [&](int sv) -> u32 {
+                if constexpr (LUT) {
+                    const int idx = min((mx - sv) >> SHIFT, lut_last);
+                    return sLUT[idx];
+                } else {
+                    return shift_exp_fixed(sv - mx, p.alpha_scaled);
                 }
+            };
+            u32 sum = 0;
+            static_for<NT>([&](auto T) {
+                constexpr int t = decltype(T)::value;
+                if (TAIL && t < NT - 1) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) { const u32 e = exp_of(s[t][r]); s[t][r] = (int)e; sum += e; }
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        u32 e = 0;
+                        if (16 * t + 4 * g + r < N) e = exp_of(s[t][r]);
+                        s[t][r] = (int)e;
+                        sum += e;
+                    }
+                }
+            });
             sum += __shfl_xor(sum, 16, 64);
             sum += __shfl_xor(sum, 32, 64);
-            // ---- P level = #{k : 2*pmax*e > (2k-1)*sum}: float estimate, exact integer fix-up -
+            // ---- P level = #{k : 2*pmax*e > (2k-1)*sum} (division absorbed into the comparator) --
+            // Cheap value x = e * (pmax/sum) in fp32 is within pmax*2^-22 of the exact ratio, and the
+            // level is that ratio rounded (exact halves down).  Unless x is that close to a half,
+            // rint(x) is the level; otherwise the four values are decided in 64-bit integers.
             const float inv = (float)p.pmax / (float)sum;
+            const float thr_p = 0.5f - (P8 ? 0x1p-13f : 0x1p-17f);
             const u32 two_pmax = 2u * (u32)p.pmax;
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
+            float worst = 0.0f;            // largest distance of a ratio from its rounded value
+            static_for<NT>([&](auto T) {
+                constexpr int t = decltype(T)::value;
                 u32 packed = 0;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const u32 e = (u32)s[t][r];
-                    u32 c = (u32)rintf((float)e * inv);
-                    const uint64_t lhs = (uint64_t)two_pmax * e;
-                    const uint64_t up = (uint64_t)(2u * c + 1u) * sum;
-                    const uint64_t dn = (uint64_t)(2u * c - 1u) * sum;   // only used when c > 0
-                    if (lhs > up) c += 1;
-                    else if (c > 0 && lhs <= dn) c -= 1;
-                    c = min(c, (u32)p.pmax);
-                    packed |= (P8 ? (c ^ 0x80u) : c) << (8 * r);
+                    const float x = (float)(u32)s[t][r] * inv;
+                    const float q = rintf(x);
+                    worst = fmaxf(worst, fabsf(x - q));
+                    packed = __builtin_amdgcn_cvt_pk_u8_f32(q, r, packed);
                 }
-                pp[t] = packed;
+                pp[t] = P8 ? (packed ^ 0x80808080u) : packed;
+            });
+            if (__builtin_amdgcn_ballot_w64(!(worst <= thr_p)) != 0) {
+                // some ratio of this 16-query block is within the error bound of a half: decide
+                // every level of the block in exact 64-bit integer arithmetic (rare)
+                static_for<NT>([&](auto T) {
+                    constexpr int t = decltype(T)::value;
+                    u32 packed = 0;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const u32 e = (u32)s[t][r];
+                        u32 c = (u32)rintf((float)e * inv);
+                        const uint64_t lhs = (uint64_t)two_pmax * e;
+                        const uint64_t up = (uint64_t)(2u * c + 1u) * sum;
+                        const uint64_t dn = (uint64_t)(2u * c - 1u) * sum;   // only used when c > 0
+                        if (lhs > up) c += 1;
+                        else if (c > 0 && lhs <= dn) c -= 1;
+                        c = min(c, (u32)p.pmax);
+                        packed |= (P8 ? (c ^ 0x80u) : c) << (8 * r);
+                    }
+                    pp[t] = packed;
+                });
             }
             if constexpr (MODE == kAttnQKOnly) {
                 if (p.p_out && qok) {
@@ -253,6 +305,12 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
                 int q16[16];
                 float of[16];
                 int oa[16];
+                // requantization: cheap value fma(o, 1/s_o, -qmin) with the same guard as the
+                // linear epilogue; a block with an element near a rounding boundary is redone
+                // with the exact division
+                const float bias8 = -p.qminf, top = p.qmaxf - p.qminf;
+                const float thr_o = 0.5f - p.eps_o;
+                bool risky_o = false;
 #pragma unroll
                 for (int T = 0; T < 4; ++T)
 #pragma unroll
@@ -260,10 +318,17 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
                         int a = o[T][r];
                         if constexpr (P8) a += 128 * cs[T][r];
                         oa[4 * T + r] = a;
-                        float ov = (float)a * p.spv;
+                        const float ov = (float)a * p.spv;
                         of[4 * T + r] = ov;
-                        q16[4 * T + r] = quantize_level(ov, p.s_o, p.qminf, p.qmaxf);
+                        const float t8 = fmaf(ov, p.r_o, bias8);
+                        const float q8 = rintf(t8);
+                        risky_o = risky_o || !(fabsf(t8 - q8) <= thr_o);
+                        q16[4 * T + r] = (int)__builtin_amdgcn_fmed3f(q8, 0.0f, top) + (int)p.qminf;
                     }
+                if (__builtin_amdgcn_ballot_w64(risky_o) != 0) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) q16[i] = quantize_level(of[i], p.s_o, p.qminf, p.qmaxf);
+                }
                 const int d0 = 16 * g;
                 if (p.o_acc_out) {
                     int4 *dst = reinterpret_cast<int4 *>(p.o_acc_out + (row0 + qrow) * 64 + d0);
@@ -292,12 +357,13 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnParams p) {
     }
 }
 
-template <int NT, int SB, int MODE, bool P8>
-hipError_t launch_one(const AttnParams &p, hipStream_t stream) {
+template <int NT, int SB, int MODE, bool P8, bool LUT, bool TAIL>
+hipError_t launch_tail(const AttnParams &p, hipStream_t stream) {
     constexpr int NCH = (NT + 3) / 4;
     constexpr int KPITCH = (SB == 4) ? 40 : 80;
-    constexpr size_t lds = ((NT * 16 * KPITCH + 15) & ~15) + (size_t)64 * (NCH * 64 + 16);
-    auto kern = attention_kernel<NT, SB, MODE, P8>;
+    const size_t lds = ((NT * 16 * KPITCH + 15) & ~15) + (size_t)64 * (NCH * 64 + 16) +
+                       (LUT ? (size_t)p.lut_n * 4 : 0);
+    auto kern = attention_kernel<NT, SB, MODE, P8, LUT, TAIL>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -308,10 +374,17 @@ hipError_t launch_one(const AttnParams &p, hipStream_t stream) {
     return hipGetLastError();
 }
 
+template <int NT, int SB, int MODE, bool P8, bool LUT>
+hipError_t launch_one(const AttnParams &p, hipStream_t stream) {
+    if (p.N > 16 * (NT - 1)) return launch_tail<NT, SB, MODE, P8, LUT, true>(p, stream);
+    return launch_tail<NT, SB, MODE, P8, LUT, false>(p, stream);
+}
+
 template <int NT, int SB, int MODE>
 hipError_t launch_p(const AttnParams &p, hipStream_t stream) {
-    if (p.pmax > 127) return launch_one<NT, SB, MODE, true>(p, stream);
-    return launch_one<NT, SB, MODE, false>(p, stream);
+    if (p.pmax > 127) return launch_one<NT, SB, MODE, true, false>(p, stream);
+    if (SB == 4 && p.lut_n > 0 && MODE != kAttnPVOnly) return launch_one<NT, SB, MODE, false, true>(p, stream);
+    return launch_one<NT, SB, MODE, false, false>(p, stream);
 }
 
 template <int NT, int SB>

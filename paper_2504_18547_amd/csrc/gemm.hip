@@ -199,7 +199,7 @@ __device__ __forceinline__ void epilogue_quant(const GemmParams &p, const v16i &
         }
         const float t8 = fmaf(g, r_y, bias8);
         const float q8 = rintf(t8);
-        risky = risky || (fabsf(t8 - q8) > thr);
+        risky = risky || !(fabsf(t8 - q8) <= thr);
         lv[r] = __builtin_amdgcn_fmed3f(q8, 0.0f, top);
     }
     if (__builtin_amdgcn_ballot_w64(risky) != 0) {
