@@ -90,6 +90,9 @@ def main():
     ap.add_argument("--batch", type=int, default=0, help="0 = the batch the configuration is quoted on")
     ap.add_argument("--sharp", action="store_true", help="sharp-attention variant of the weights")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three 1 GiB device-to-device copies before the steps (a kernel of known "
+                         "traffic, used to scale the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (every image is independent; see DESIGN.md "
@@ -148,6 +151,13 @@ def main():
         vitq.vq_quantize(tokens, st["s_x"], None, xq)
         vitq.vq_attention_block(desc, xq, B, y, ws)
 
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(W):
         step()
     torch.cuda.synchronize()

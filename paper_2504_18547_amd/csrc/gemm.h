@@ -21,6 +21,7 @@ struct GemmParams {
     float r_y[3]; float eps0; float gelu_guard;
     // head-major output of the QKV linear: channel -> (q/k/v, head, d), token -> (image, n)
     int head_major; int D, dh, Ntok, Bimg, Hh;
+    int dh_shift; float inv_ntok;                    // filled by gemm_launch
 };
 
 // wb / ab: storage bits of the weight / activation operand.  Supported: (4,4) (2,4) (8,8).

@@ -52,18 +52,24 @@ __device__ __forceinline__ void store_packed16(uint8_t *dst, const int (&q)[16])
 }
 
 // Destination of this lane's 16 packed levels; nullptr if nothing is to be stored.
+// Head-major mode: channel -> (q/k/v, head, d), token -> (image, n).  The two divisions are
+// done without the integer-division expansion: the channel one by comparisons (3D channels) and
+// a shift when the head size is a power of two; the token one by an fp32 reciprocal with a
+// one-step correction (exact for m < 2^22).
 __device__ __forceinline__ uint8_t *packed_dst(const GemmParams &p, int m, int cb, int &which) {
     which = 0;
     if (p.head_major) {
         if (cb >= p.Nout) return nullptr;
-        // channel -> (q/k/v, head, d); token -> (image, n)
-        which = cb / p.D;
-        int rem = cb - which * p.D;
-        int h = rem / p.dh;
-        int d = rem - h * p.dh;
-        int b = m / p.Ntok;
+        which = (cb >= p.D ? 1 : 0) + (cb >= 2 * p.D ? 1 : 0);
+        const int rem = cb - which * p.D;
+        int h, d;
+        if (p.dh_shift >= 0) { h = rem >> p.dh_shift; d = rem & (p.dh - 1); }
+        else { h = rem / p.dh; d = rem - h * p.dh; }
+        int b = (int)((float)m * p.inv_ntok);
         int n = m - b * p.Ntok;
-        int64_t row = (((int64_t)which * p.Bimg + b) * p.Hh + h) * p.Ntok + n;
+        if (n < 0) { b -= 1; n += p.Ntok; }
+        if (n >= p.Ntok) { b += 1; n -= p.Ntok; }
+        const int64_t row = (((int64_t)which * p.Bimg + b) * p.Hh + h) * p.Ntok + n;
         return p.yq + row * p.yq_stride + ((d * p.yq_sb) >> 3);
     }
     if (((cb * p.yq_sb) >> 3) >= p.yq_row_bytes16) return nullptr;
@@ -194,8 +200,7 @@ __device__ __forceinline__ void epilogue_quant(const GemmParams &p, const v16i &
             const float X = __builtin_amdgcn_exp2f(w * y);
             const float rc = __builtin_amdgcn_rcpf(1.0f + X);
             g = fmaf(-y, rc, y);
-            const float ay = fabsf(y);
-            thr = fmaf(-(ay * fmaxf(ay, 1.0f)), gguard, thr0);
+            thr = fmaf(-(fabsf(y) + y2), gguard, thr0);     // |y| + y^2 >= |y| * max(1, |y|)
         }
         const float t8 = fmaf(g, r_y, bias8);
         const float q8 = rintf(t8);
@@ -501,6 +506,13 @@ hipError_t gemm_launch(GemmParams p, int wb, int ab, hipStream_t stream) {
     if (aligned && !p.acc_out) {
         if (p.y_out && !p.yq && p.act == 0 && p.vec_ok) epi = kEpiF32;
         if (p.yq && !p.y_out && (p.yq_sb == 4 || p.yq_sb == 8)) epi = p.act == 1 ? kEpiQuantGelu : kEpiQuant;
+    }
+    if (p.head_major) {
+        p.inv_ntok = 1.0f / (float)p.Ntok;
+        p.dh_shift = -1;
+        for (int sft = 0; sft < 16; ++sft)
+            if ((1 << sft) == p.dh) p.dh_shift = sft;
+        if (p.M >= (1 << 22)) return hipErrorInvalidValue;
     }
     if (p.yq) {
         for (int i = 0; i < 3; ++i) p.r_y[i] = 1.0f / p.s_y[i];
