@@ -25,6 +25,10 @@ namespace vitq {
 
 namespace {
 
+#ifndef VITQ_S
+#define VITQ_S 3
+#define VITQ_OCC 3
+#endif
 enum Epi { kEpiGeneric = 0, kEpiF32 = 1, kEpiQuant = 2, kEpiQuantGelu = 3 };
 
 // channel c (0..31 within a 32-block) -> MFMA row slot, chosen so that a lane's sixteen
@@ -138,29 +142,26 @@ __device__ __forceinline__ void epilogue_generic(const GemmParams &p, const v16i
     }
 }
 
-// ---- fp32-only epilogue (Nout % 16 == 0, aligned): convert, one fma, store --------------------
+// ---- fp32-only epilogue (Nout % 16 == 0) -------------------------------------------------------
+// This epilogue runs with the MFMA roles SWAPPED (tokens on the A side, weight rows on the B
+// side, weight rows unpermuted in LDS): a lane then holds ONE channel of sixteen tokens, and
+// register r of the wave is 32 consecutive channels (one full 128-byte line) of tokens
+// m0 + 8*(r/4) + r%4 (+4 for the upper half-wave).  Every store instruction therefore writes
+// two complete lines instead of 64 scattered 16-byte pieces.
 // scs = sc * 2^-shift exactly, so fma((float)acc_scaled, scs, b) == fma((float)acc, sc, b).
-__device__ __forceinline__ void epilogue_f32(const GemmParams &p, const v16i &acc, int shift, int m, int cb,
-                                             const float (&scs)[16], const float (&bs)[16], bool fold_ok) {
-    if (m >= p.M || cb >= p.Nout) return;
-    if (!fold_ok) {   // subnormal-small scales: shift first, then the unfolded scale
-        float *out = p.y_out + (int64_t)m * p.Nout + cb;
+__device__ __forceinline__ void epilogue_f32(const GemmParams &p, const v16i &acc, int shift, int m0, int ch,
+                                             float scs, float bs, bool fold_ok) {
+    if (ch >= p.Nout) return;
+    float sc = scs;
+    if (!fold_ok) sc = p.s_x * p.s_w[p.s_w_per_channel ? ch : 0];   // subnormal-small scales: unfolded
+    float *out = p.y_out + (int64_t)m0 * p.Nout + ch;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const float sc = p.s_x * p.s_w[p.s_w_per_channel ? cb + r : 0];
-            out[r] = fmaf((float)(acc[r] >> shift), sc, bs[r]);
+    for (int r = 0; r < 16; ++r) {
+        const int dm = 8 * (r >> 2) + (r & 3);
+        if (m0 + dm < p.M) {
+            const int a = fold_ok ? acc[r] : (acc[r] >> shift);
+            out[(int64_t)dm * p.Nout] = fmaf((float)a, sc, bs);
         }
-        return;
-    }
-    float4 *dst = reinterpret_cast<float4 *>(p.y_out + (int64_t)m * p.Nout + cb);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        float4 v;
-        v.x = fmaf((float)acc[4 * j + 0], scs[4 * j + 0], bs[4 * j + 0]);
-        v.y = fmaf((float)acc[4 * j + 1], scs[4 * j + 1], bs[4 * j + 1]);
-        v.z = fmaf((float)acc[4 * j + 2], scs[4 * j + 2], bs[4 * j + 2]);
-        v.w = fmaf((float)acc[4 * j + 3], scs[4 * j + 3], bs[4 * j + 3]);
-        dst[j] = v;
     }
 }
 
@@ -250,30 +251,75 @@ __device__ __forceinline__ void epilogue_quant(const GemmParams &p, const v16i &
     }
 }
 
+// ---- direct global -> LDS loads ----------------------------------------------------------------
+// global_load_lds_dwordx4: lane i of the wave writes its 16 bytes to LDS address M0 + 16*i; no
+// VGPRs are used for the data, so several k-stages can be in flight at once.  The compiler does
+// not see these loads: completion is tracked by hand with s_waitcnt vmcnt(n) (loads retire in
+// order), followed by a workgroup barrier before any lane reads the stage.
+__device__ __forceinline__ u32 lds_address(const void *p) {
+    return (u32)(uintptr_t)(const __attribute__((address_space(3))) uint8_t *)p;
+}
+// address = sbase (uniform) + voff (per lane)
+__device__ __forceinline__ void dma16(u32 voff, const uint8_t *sbase, u32 lds_dst) {
+    u32 keep;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %1, %2\n\ts_mov_b32 m0, %0"
+                 : "=&s"(keep) : "v"(voff), "s"(sbase), "s"(lds_dst) : "memory");
+}
+// address = per-lane pointer
+__device__ __forceinline__ void dma16_ptr(const uint8_t *ptr, u32 lds_dst) {
+    u32 keep;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+                 : "=&s"(keep) : "v"(ptr), "s"(lds_dst) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+
+// sixteen zero bytes: the source of operand chunks that lie beyond the end of a row (K tail)
+__device__ __attribute__((aligned(16))) const u32 g_zero16[4] = {0u, 0u, 0u, 0u};
+
+// XOR swizzle of the 16-byte chunk index inside an LDS row of CH chunks (rows are stored without
+// padding): spreads the rows that consecutive lanes read over all banks.
+template <int CH>
+__device__ __forceinline__ int swz(int row) {
+    if constexpr (CH == 4) return ((row >> 2) & 3) ^ (row & 2);
+    else if constexpr (CH == 8) return row & 7;
+    else if constexpr (CH == 2) return (row >> 2) & 1;
+    else return 0;
+}
+
+// inverse of slot_of_channel
+__device__ __forceinline__ int channel_of_slot(int s) {
+    return 16 * ((s >> 2) & 1) + 4 * (s >> 3) + (s & 3);
+}
+
 template <int WB, int AB, int TC, int TT, int WAVES_C, int WAVES_T, int BK, int EPI>
-__global__ __launch_bounds__(WAVES_C *WAVES_T * 64, ((TC / WAVES_C) * (TT / WAVES_T) <= 8192 ? 2 : 1))
+__global__ __launch_bounds__(WAVES_C *WAVES_T * 64, VITQ_OCC)
 void gemm_kernel(GemmParams p) {
     constexpr int NT = WAVES_C * WAVES_T * 64;
+    constexpr int S = VITQ_S;                                      // k-stages resident in LDS
     constexpr int WROW = BK * WB / 8, XROW = BK * AB / 8;     // bytes per row per stage
-    constexpr int WPITCH = WROW + 16, XPITCH = XROW + 16;     // LDS row pitch (bank spread)
     constexpr int WCH = WROW / 16, XCH = XROW / 16;           // 16-byte chunks per row
     constexpr int W_ITERS = TC * WCH / NT, X_ITERS = TT * XCH / NT;
     static_assert((TC * WCH) % NT == 0 && (TT * XCH) % NT == 0, "tile/threads mismatch");
+    constexpr int LOADS = W_ITERS + X_ITERS;                  // loads per lane per stage
     constexpr int WC = TC / WAVES_C, WT = TT / WAVES_T;       // wave tile
     constexpr int NC = WC / 32, NTK = WT / 32;                // 32x32 blocks per wave
     static_assert(WC % 32 == 0 && WT % 32 == 0 && TC % 64 == 0 && BK % 64 == 0, "wave tile");
-    constexpr int WBUF = TC * WPITCH, XBUF = TT * XPITCH;
+    constexpr int WBUF = TC * WROW, XBUF = TT * XROW, STAGE = WBUF + XBUF;
+    constexpr bool SWAP = (EPI == kEpiF32);   // tokens as the MFMA A operand (see epilogue_f32)
 
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    uint8_t *sW = smem;
-    uint8_t *sX = smem + 2 * WBUF;
-    float *s_scs = reinterpret_cast<float *>(smem + 2 * (WBUF + XBUF));   // [TC] folded scales
+    float *s_scs = reinterpret_cast<float *>(smem + S * STAGE);           // [TC] folded scales
     float *s_bs = s_scs + TC;                                             // [TC] biases
     int *s_fold_bad = reinterpret_cast<int *>(s_bs + TC);                 // [1] flag
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wave_c = wave % WAVES_C;
     const int wave_t = wave / WAVES_C;
     const int li = lane & 31;   // MFMA row / column index of this lane
@@ -294,6 +340,66 @@ void gemm_kernel(GemmParams p) {
     const int tt = logical / n_ct;
     const int c0 = ct * TC;
     const int t0 = tt * TT;
+
+    // ---- stage loads: what each lane fetches is fixed; only the k offset (uniform) advances ----
+    // LDS position pos (16-byte units) of a tile holds row pos / CH, chunk (pos % CH) ^ swz(row).
+    // Weight rows sit in permuted slots (slot_of_channel) unless the roles are swapped.  Rows
+    // beyond the matrix are clamped to its last row: their products land in accumulators that
+    // are never stored.
+    const int nk = (p.K + BK - 1) / BK;
+    const bool ktail = (nk * WROW > p.kbytes_w16) || (nk * XROW > p.kbytes_x16);
+    const uint8_t *wbase = p.w + (int64_t)c0 * p.w_stride;
+    const uint8_t *xbase = p.x + (int64_t)t0 * p.x_stride;
+    u32 w_off[W_ITERS], x_off[X_ITERS];
+    int w_kb[W_ITERS], x_kb[X_ITERS];
+#pragma unroll
+    for (int it = 0; it < W_ITERS; ++it) {
+        const int pos = it * NT + tid;
+        const int slot = pos / WCH;
+        const int chunk = (pos % WCH) ^ swz<WCH>(slot);
+        int row = SWAP ? slot : ((slot & ~31) | channel_of_slot(slot & 31));
+        row = min(row, p.Nout - 1 - c0);
+        w_off[it] = (u32)row * (u32)p.w_stride + (u32)chunk * 16u;
+        w_kb[it] = chunk * 16;
+    }
+#pragma unroll
+    for (int it = 0; it < X_ITERS; ++it) {
+        const int pos = it * NT + tid;
+        int row = pos / XCH;
+        const int chunk = (pos % XCH) ^ swz<XCH>(row);
+        row = min(row, p.M - 1 - t0);
+        x_off[it] = (u32)row * (u32)p.x_stride + (u32)chunk * 16u;
+        x_kb[it] = chunk * 16;
+    }
+    const u32 lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem)) + (u32)wave * 1024u;
+    auto issue = [&](int kt) {
+        const u32 dst = lds0 + (u32)(kt % S) * STAGE;
+        if (ktail && kt == nk - 1) {
+            // last stage of a K that does not fill it: chunks past the row end come from zeros
+#pragma unroll
+            for (int it = 0; it < W_ITERS; ++it) {
+                const uint8_t *src = wbase + (int64_t)kt * WROW + w_off[it];
+                if (kt * WROW + w_kb[it] >= p.kbytes_w16) src = reinterpret_cast<const uint8_t *>(g_zero16);
+                dma16_ptr(src, dst + it * (NT * 16));
+            }
+#pragma unroll
+            for (int it = 0; it < X_ITERS; ++it) {
+                const uint8_t *src = xbase + (int64_t)kt * XROW + x_off[it];
+                if (kt * XROW + x_kb[it] >= p.kbytes_x16) src = reinterpret_cast<const uint8_t *>(g_zero16);
+                dma16_ptr(src, dst + WBUF + it * (NT * 16));
+            }
+        } else {
+            const uint8_t *wk = wbase + (int64_t)kt * WROW;
+            const uint8_t *xk = xbase + (int64_t)kt * XROW;
+#pragma unroll
+            for (int it = 0; it < W_ITERS; ++it) dma16(w_off[it], wk, dst + it * (NT * 16));
+#pragma unroll
+            for (int it = 0; it < X_ITERS; ++it) dma16(x_off[it], xk, dst + WBUF + it * (NT * 16));
+        }
+    };
+#pragma unroll
+    for (int st = 0; st < S - 1; ++st)
+        if (st < nk) issue(st);
 
     // Per-channel epilogue constants, staged once per tile while the first operand loads are in
     // flight: sc = s_x*s_w[c] (the definition's exact product) with the operand factor 2^shift
@@ -322,59 +428,34 @@ void gemm_kernel(GemmParams p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    uint4 wreg[W_ITERS], xreg[X_ITERS];
-
-    auto gload = [&](int kt) {
+    // Byte offsets (inside a stage) of this lane's operand reads.  In sub-step ss the lane owns the
+    // 32 values [64*ss + 32*g, +32) of its row: two MFMA operands of 16 values each.
+    constexpr int NSS = BK / 64;
+    constexpr int WRD = (WB == 8) ? 2 : 1, XRD = (AB == 8) ? 2 : 1;      // 16-byte reads per sub-step
+    u32 w_rd[NSS][WRD], x_rd[NSS][XRD];
+    {
+        const int wrow = wave_c * WC + li, xrow = wave_t * WT + li;
 #pragma unroll
-        for (int it = 0; it < W_ITERS; ++it) {
-            int id = it * NT + tid;
-            int row = id / WCH, ch = id % WCH;
-            int gr = c0 + row;
-            int kb = kt * WROW + ch * 16;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (gr < p.Nout && kb < p.kbytes_w16)
-                v = *reinterpret_cast<const uint4 *>(p.w + (int64_t)gr * p.w_stride + kb);
-            wreg[it] = v;
-        }
+        for (int ss = 0; ss < NSS; ++ss) {
+            const int wbo = ((ss * 64 + g * 32) * WB) / 8, xbo = ((ss * 64 + g * 32) * AB) / 8;
 #pragma unroll
-        for (int it = 0; it < X_ITERS; ++it) {
-            int id = it * NT + tid;
-            int row = id / XCH, ch = id % XCH;
-            int gr = t0 + row;
-            int kb = kt * XROW + ch * 16;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (gr < p.M && kb < p.kbytes_x16)
-                v = *reinterpret_cast<const uint4 *>(p.x + (int64_t)gr * p.x_stride + kb);
-            xreg[it] = v;
-        }
-    };
-    auto sstore = [&](int buf) {
+            for (int j = 0; j < WRD; ++j)
+                w_rd[ss][j] = (u32)((wrow * WCH + (((wbo >> 4) + j) ^ swz<WCH>(wrow))) * 16 + (wbo & 15));
 #pragma unroll
-        for (int it = 0; it < W_ITERS; ++it) {
-            int id = it * NT + tid;
-            int row = id / WCH, ch = id % WCH;
-            int slot = (row & ~31) | slot_of_channel(row & 31);
-            *reinterpret_cast<uint4 *>(sW + buf * WBUF + slot * WPITCH + ch * 16) = wreg[it];
+            for (int j = 0; j < XRD; ++j)
+                x_rd[ss][j] = (u32)(WBUF + (xrow * XCH + (((xbo >> 4) + j) ^ swz<XCH>(xrow))) * 16 + (xbo & 15));
         }
-#pragma unroll
-        for (int it = 0; it < X_ITERS; ++it) {
-            int id = it * NT + tid;
-            int row = id / XCH, ch = id % XCH;
-            *reinterpret_cast<uint4 *>(sX + buf * XBUF + row * XPITCH + ch * 16) = xreg[it];
-        }
-    };
+    }
     auto compute = [&](int buf) {
-        const uint8_t *bw = sW + buf * WBUF + (wave_c * WC + li) * WPITCH;
-        const uint8_t *bx = sX + buf * XBUF + (wave_t * WT + li) * XPITCH;
+        const uint8_t *stage = smem + buf * STAGE;
 #pragma unroll
-        for (int ss = 0; ss < BK / 64; ++ss) {
-            // lane g owns values [64*ss + 32*g, +32): two MFMA operands of 16 values each,
-            // fetched packed with one LDS read and unpacked one operand at a time
+        for (int ss = 0; ss < NSS; ++ss) {
+            // operands are fetched packed and unpacked one MFMA operand at a time
             constexpr int WRAW = (32 * WB) / 32, XRAW = (32 * AB) / 32;   // dwords per lane
             u32 wr[NC][WRAW], xr[NTK][XRAW];
 #pragma unroll
             for (int ci = 0; ci < NC; ++ci) {
-                const uint8_t *src = bw + ci * 32 * WPITCH + ((ss * 64 + g * 32) * WB) / 8;
+                const uint8_t *src = stage + w_rd[ss][0] + ci * 32 * WROW;
                 if constexpr (WB == 4) {
                     uint4 v = *reinterpret_cast<const uint4 *>(src);
                     wr[ci][0] = v.x; wr[ci][1] = v.y; wr[ci][2] = v.z; wr[ci][3] = v.w;
@@ -383,20 +464,20 @@ void gemm_kernel(GemmParams p) {
                     wr[ci][0] = v.x; wr[ci][1] = v.y;
                 } else {
                     uint4 v0 = *reinterpret_cast<const uint4 *>(src);
-                    uint4 v1 = *reinterpret_cast<const uint4 *>(src + 16);
+                    uint4 v1 = *reinterpret_cast<const uint4 *>(stage + w_rd[ss][WRD - 1] + ci * 32 * WROW);
                     wr[ci][0] = v0.x; wr[ci][1] = v0.y; wr[ci][2] = v0.z; wr[ci][3] = v0.w;
                     wr[ci][4] = v1.x; wr[ci][5] = v1.y; wr[ci][6] = v1.z; wr[ci][7] = v1.w;
                 }
             }
 #pragma unroll
             for (int ti = 0; ti < NTK; ++ti) {
-                const uint8_t *src = bx + ti * 32 * XPITCH + ((ss * 64 + g * 32) * AB) / 8;
+                const uint8_t *src = stage + x_rd[ss][0] + ti * 32 * XROW;
                 if constexpr (AB == 4) {
                     uint4 v = *reinterpret_cast<const uint4 *>(src);
                     xr[ti][0] = v.x; xr[ti][1] = v.y; xr[ti][2] = v.z; xr[ti][3] = v.w;
                 } else {
                     uint4 v0 = *reinterpret_cast<const uint4 *>(src);
-                    uint4 v1 = *reinterpret_cast<const uint4 *>(src + 16);
+                    uint4 v1 = *reinterpret_cast<const uint4 *>(stage + x_rd[ss][XRD - 1] + ti * 32 * XROW);
                     xr[ti][0] = v0.x; xr[ti][1] = v0.y; xr[ti][2] = v0.z; xr[ti][3] = v0.w;
                     xr[ti][4] = v1.x; xr[ti][5] = v1.y; xr[ti][6] = v1.z; xr[ti][7] = v1.w;
                 }
@@ -425,55 +506,71 @@ void gemm_kernel(GemmParams p) {
                 for (int ci = 0; ci < NC; ++ci)
 #pragma unroll
                     for (int ti = 0; ti < NTK; ++ti)
-                        acc[ci][ti] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[ci], xf[ti], acc[ci][ti], 0, 0, 0);
+                        if constexpr (SWAP)
+                            acc[ci][ti] = __builtin_amdgcn_mfma_i32_32x32x32_i8(xf[ti], wf[ci], acc[ci][ti], 0, 0, 0);
+                        else
+                            acc[ci][ti] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[ci], xf[ti], acc[ci][ti], 0, 0, 0);
             }
         }
     };
 
-    const int nk = (p.K + BK - 1) / BK;
-    gload(0);
-    sstore(0);
-    __syncthreads();
+    // Stage kt is complete once all but the loads of the (at most S-2) younger stages have
+    // retired; the barrier then also tells that every wave has finished reading stage kt-1, whose
+    // buffer the next issue overwrites.
     for (int kt = 0; kt < nk; ++kt) {
-        const bool more = kt + 1 < nk;
-        if (more) gload(kt + 1);
-        compute(kt & 1);
-        if (more) sstore((kt + 1) & 1);
+        const int younger = nk - 1 - kt;
+        if (younger >= S - 2) wait_vmcnt<(S - 2) * LOADS>();
+        else if (younger == 1) wait_vmcnt<LOADS>();
+        else wait_vmcnt<0>();
         __syncthreads();
+        if (kt + S - 1 < nk) issue(kt + S - 1);
+        compute(kt % S);
     }
+    __syncthreads();
 
     // ---- epilogue -------------------------------------------------------------------------
     constexpr int shift = Shift<WB, AB>::value;
     const bool fold_ok = (EPI != kEpiGeneric) && (s_fold_bad[0] == 0);
-    static_for<NC>([&](auto CI) {
-        constexpr int ci = decltype(CI)::value;
-        const int cl = wave_c * WC + ci * 32 + 16 * g;     // channel offset inside the tile
-        const int cb = c0 + cl;
-        float bs[16], scs[16];
-        if constexpr (EPI != kEpiGeneric) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float4 a = *reinterpret_cast<const float4 *>(s_scs + cl + 4 * j);
-                const float4 b = *reinterpret_cast<const float4 *>(s_bs + cl + 4 * j);
-                scs[4 * j] = a.x; scs[4 * j + 1] = a.y; scs[4 * j + 2] = a.z; scs[4 * j + 3] = a.w;
-                bs[4 * j] = b.x; bs[4 * j + 1] = b.y; bs[4 * j + 2] = b.z; bs[4 * j + 3] = b.w;
-            }
-        }
-        static_for<NTK>([&](auto TI) {
-            constexpr int ti = decltype(TI)::value;
-            const int m = t0 + wave_t * WT + ti * 32 + li;
-            if constexpr (EPI == kEpiF32) epilogue_f32(p, acc[ci][ti], shift, m, cb, scs, bs, fold_ok);
-            else if constexpr (EPI == kEpiQuant) epilogue_quant<false>(p, acc[ci][ti], shift, m, cb, scs, bs, !fold_ok);
-            else if constexpr (EPI == kEpiQuantGelu) epilogue_quant<true>(p, acc[ci][ti], shift, m, cb, scs, bs, !fold_ok);
-            else epilogue_generic(p, acc[ci][ti], shift, m, cb);
+    if constexpr (SWAP) {
+        static_for<NC>([&](auto CI) {
+            constexpr int ci = decltype(CI)::value;
+            const int cl = wave_c * WC + ci * 32 + li;     // this lane's channel inside the tile
+            const float scs = s_scs[cl], bs = s_bs[cl];
+            static_for<NTK>([&](auto TI) {
+                constexpr int ti = decltype(TI)::value;
+                const int m0 = t0 + wave_t * WT + ti * 32 + 4 * g;
+                epilogue_f32(p, acc[ci][ti], shift, m0, c0 + cl, scs, bs, fold_ok);
+            });
         });
-    });
+    } else {
+        static_for<NC>([&](auto CI) {
+            constexpr int ci = decltype(CI)::value;
+            const int cl = wave_c * WC + ci * 32 + 16 * g;     // channel offset inside the tile
+            const int cb = c0 + cl;
+            float bs[16], scs[16];
+            if constexpr (EPI != kEpiGeneric) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float4 a = *reinterpret_cast<const float4 *>(s_scs + cl + 4 * j);
+                    const float4 b = *reinterpret_cast<const float4 *>(s_bs + cl + 4 * j);
+                    scs[4 * j] = a.x; scs[4 * j + 1] = a.y; scs[4 * j + 2] = a.z; scs[4 * j + 3] = a.w;
+                    bs[4 * j] = b.x; bs[4 * j + 1] = b.y; bs[4 * j + 2] = b.z; bs[4 * j + 3] = b.w;
+                }
+            }
+            static_for<NTK>([&](auto TI) {
+                constexpr int ti = decltype(TI)::value;
+                const int m = t0 + wave_t * WT + ti * 32 + li;
+                if constexpr (EPI == kEpiQuant) epilogue_quant<false>(p, acc[ci][ti], shift, m, cb, scs, bs, !fold_ok);
+                else if constexpr (EPI == kEpiQuantGelu) epilogue_quant<true>(p, acc[ci][ti], shift, m, cb, scs, bs, !fold_ok);
+                else epilogue_generic(p, acc[ci][ti], shift, m, cb);
+            });
+        });
+    }
 }
 
 template <int WB, int AB, int TC, int TT, int WAVES_C, int WAVES_T, int BK, int EPI>
 hipError_t launch(const GemmParams &p, hipStream_t stream) {
-    constexpr int WPITCH = BK * WB / 8 + 16, XPITCH = BK * AB / 8 + 16;
-    constexpr size_t lds = 2 * ((size_t)TC * WPITCH + (size_t)TT * XPITCH) + 2 * TC * sizeof(float) + 16;
+    constexpr size_t lds = VITQ_S * ((size_t)TC * (BK * WB / 8) + (size_t)TT * (BK * AB / 8)) + 2 * TC * sizeof(float) + 16;
     auto kern = gemm_kernel<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, EPI>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -503,10 +600,12 @@ hipError_t gemm_launch(GemmParams p, int wb, int ab, hipStream_t stream) {
     // pick the epilogue: the specialised ones need full 16-channel groups and a single output
     int epi = kEpiGeneric;
     const bool aligned = (p.Nout % 16 == 0);
+    if (!p.acc_out && p.y_out && !p.yq && p.act == 0) epi = kEpiF32;     // any Nout
     if (aligned && !p.acc_out) {
-        if (p.y_out && !p.yq && p.act == 0 && p.vec_ok) epi = kEpiF32;
         if (p.yq && !p.y_out && (p.yq_sb == 4 || p.yq_sb == 8)) epi = p.act == 1 ? kEpiQuantGelu : kEpiQuant;
     }
+    // per-lane operand offsets inside a tile are kept in 32 bits (127 rows * stride + 112)
+    if (p.x_stride >= (1 << 24) || p.w_stride >= (1 << 24) || p.M < 1 || p.Nout < 1) return hipErrorInvalidValue;
     if (p.head_major) {
         p.inv_ntok = 1.0f / (float)p.Ntok;
         p.dh_shift = -1;
@@ -524,7 +623,7 @@ hipError_t gemm_launch(GemmParams p, int wb, int ab, hipStream_t stream) {
     }
     if (wb == 4 && ab == 4) return launch_epi<4, 4, 128, 128, 2, 2, 128>(p, epi, stream);
     if (wb == 2 && ab == 4) return launch_epi<2, 4, 128, 128, 2, 2, 128>(p, epi, stream);
-    if (wb == 8 && ab == 8) return launch_epi<8, 8, 128, 128, 2, 2, 128>(p, epi, stream);
+    if (wb == 8 && ab == 8) return launch_epi<8, 8, 128, 128, 2, 2, 64>(p, epi, stream);
     return hipErrorInvalidValue;
 }
 
