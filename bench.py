@@ -90,6 +90,9 @@ def main():
     ap.add_argument("--batch", type=int, default=0, help="0 = the batch the configuration is quoted on")
     ap.add_argument("--sharp", action="store_true", help="sharp-attention variant of the weights")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--prepack", action="store_true",
+                    help="give the block the expanded int8 weight copies made once by vq_prepack_weight "
+                         "instead of letting every GEMM tile unpack the packed weights itself")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three 1 GiB device-to-device copies before the steps (a kernel of known "
                          "traffic, used to scale the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -125,6 +128,8 @@ def main():
         vitq.vq_quantize(w, 0.0, s, q)
         wd["w_" + nm], wd["sw_" + nm] = q, s
         wd["b_" + nm] = torch.from_numpy(w_fp["b_" + nm]).cuda()
+        if args.prepack and q.storage_bits in (2, 4) and sa == 4:
+            wd["wp_" + nm] = vitq.vq_prepack_weight(q)      # offline weight preparation, like quantizing them
     tokens = torch.empty((B * N, D), dtype=torch.float32, device="cuda")
     for b0 in range(0, B, 32):
         imgs = list(range(b0, min(B, b0 + 32)))

@@ -163,7 +163,33 @@ typedef struct vq_block_desc {
      * stream before the first stage and event i after stage i (1 QKV linear, 2 attention,
      * 3 projection, 4 fc1, 5 fc2); 4 events are used when hidden == 0, else 6.              */
     void **stage_events;
+    /* Optional expanded copies of the four weight matrices made by vq_prepack_weight (device,
+     * nullable, all four or none; hidden == 0: the first two).  With 4-bit activation storage
+     * the linears then read these instead of unpacking the packed weights in every tile.     */
+    const void *wp_qkv, *wp_proj, *wp_fc1, *wp_fc2;
 } vq_block_desc;
+
+/*
+ * Offline weight preparation (optional).  The packed format above is the interchange format;
+ * the matrix cores consume int8, so a 2-/3-/4-bit weight matrix is expanded either inside every
+ * GEMM tile that uses it, or once, here: `out` receives an int8 copy [rows x kp], kp = cols
+ * rounded up to 16, values in the operand order of the GEMM kernels (opaque to the caller),
+ * zero beyond cols.  The products, and therefore every result, are identical (Eq. 2 is an
+ * exact integer contraction either way).
+ * w: packed weights, storage_bits 2 or 4 (else VQ_ERR_UNSUPPORTED).  out: device, 16-byte
+ * aligned, at least the size vq_prepack_weight_bytes reports (else VQ_ERR_WORKSPACE).
+ */
+vq_status vq_prepack_weight_bytes(const vq_qmat *w, size_t *bytes);
+vq_status vq_prepack_weight(const vq_qmat *w, void *out, size_t out_bytes, void *stream);
+
+/*
+ * vq_linear with the expanded weight copy `wp` of the same `wq` (made by vq_prepack_weight).
+ * xq must use 4-bit storage.  Everything else as vq_linear; results are identical to it.
+ */
+vq_status vq_linear_prepacked(const vq_qmat *xq, float s_x, const vq_qmat *wq, const void *wp,
+                              const float *s_w, int32_t s_w_per_channel, const float *bias,
+                              int32_t act, int32_t *acc_out, float *y_out, float s_y,
+                              const vq_qmat *yq_out, void *stream);
 
 /* Bytes of workspace vq_attention_block needs for batch B (host computation only). */
 vq_status vq_attention_block_workspace(const vq_block_desc *desc, int64_t B, size_t *bytes);

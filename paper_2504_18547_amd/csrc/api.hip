@@ -50,7 +50,8 @@ struct LinearExtra {      // head-major output of the QKV linear inside the bloc
 // Shared by vq_linear and vq_attention_block; all descriptors already validated.
 vq_status run_linear(const vq_qmat *xq, float s_x, const vq_qmat *wq, const float *s_w,
                      int per_channel, const float *bias, int act, int32_t *acc_out, float *y_out,
-                     float s_y, const vq_qmat *yq_out, const LinearExtra *ex, hipStream_t stream) {
+                     float s_y, const vq_qmat *yq_out, const LinearExtra *ex, hipStream_t stream,
+                     const void *wp = nullptr) {
     GemmParams p{};
     p.x = (const uint8_t *)xq->data; p.x_stride = xq->row_stride; p.M = (int)xq->rows;
     p.w = (const uint8_t *)wq->data; p.w_stride = wq->row_stride; p.Nout = (int)wq->rows;
@@ -74,7 +75,14 @@ vq_status run_linear(const vq_qmat *xq, float s_x, const vq_qmat *wq, const floa
         level_range(yq_out->bits, &p.qminf, &p.qmaxf);
     }
     if (p.M == 0 || p.Nout == 0) return VQ_OK;
-    hipError_t e = gemm_launch(p, wq->storage_bits, xq->storage_bits, stream);
+    int wb = wq->storage_bits;
+    if (wp && xq->storage_bits == 4 && (wb == 2 || wb == 4)) {
+        // expanded int8 copy of the same weights: same products, no unpacking of W in the tiles
+        const int64_t kp = (wq->cols + 15) / 16 * 16;
+        p.w = (const uint8_t *)wp; p.w_stride = kp; p.kbytes_w16 = (int)kp;
+        wb = 8;
+    }
+    hipError_t e = gemm_launch(p, wb, xq->storage_bits, stream);
     return e == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }
 
@@ -185,6 +193,48 @@ vq_status vq_linear(const vq_qmat *xq, float s_x, const vq_qmat *wq, const float
     }
     return run_linear(xq, s_x, wq, s_w, s_w_per_channel ? 1 : 0, bias, act, acc_out, y_out, s_y, yq_out,
                       nullptr, (hipStream_t)stream);
+}
+
+vq_status vq_prepack_weight_bytes(const vq_qmat *w, size_t *bytes) {
+    if (!bytes) return VQ_ERR_NULL;
+    vq_status st = check_qmat(w, 0);
+    if (st != VQ_OK) return st;
+    if (w->storage_bits != 2 && w->storage_bits != 4) return VQ_ERR_UNSUPPORTED;
+    *bytes = (size_t)w->rows * (size_t)((w->cols + 15) / 16 * 16);
+    return VQ_OK;
+}
+
+vq_status vq_prepack_weight(const vq_qmat *w, void *out, size_t out_bytes, void *stream) {
+    size_t need = 0;
+    vq_status st = vq_prepack_weight_bytes(w, &need);
+    if (st != VQ_OK) return st;
+    if (need == 0) return VQ_OK;
+    if (!out) return VQ_ERR_NULL;
+    if (out_bytes < need || ((uintptr_t)out) % 16 != 0) return VQ_ERR_WORKSPACE;
+    hipError_t e = prepack_launch((const uint8_t *)w->data, w->rows, w->cols, w->row_stride, w->storage_bits,
+                                  (int8_t *)out, (w->cols + 15) / 16 * 16, (hipStream_t)stream);
+    return e == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
+vq_status vq_linear_prepacked(const vq_qmat *xq, float s_x, const vq_qmat *wq, const void *wp,
+                              const float *s_w, int32_t s_w_per_channel, const float *bias, int32_t act,
+                              int32_t *acc_out, float *y_out, float s_y, const vq_qmat *yq_out,
+                              void *stream) {
+    vq_status st = check_linear_operands(xq, wq);
+    if (st != VQ_OK) return st;
+    if (!s_w || !wp) return VQ_ERR_NULL;
+    if (xq->storage_bits != 4 || (wq->storage_bits != 2 && wq->storage_bits != 4)) return VQ_ERR_UNSUPPORTED;
+    if (((uintptr_t)wp) % 16 != 0) return VQ_ERR_STRIDE;
+    if (!acc_out && !y_out && !yq_out) return VQ_ERR_NULL;
+    if (act != 0 && act != 1) return VQ_ERR_UNSUPPORTED;
+    if (!good_step(s_x)) return VQ_ERR_STEP;
+    if (yq_out) {
+        if ((st = check_qmat(yq_out, 0)) != VQ_OK) return st;
+        if (yq_out->rows != xq->rows || yq_out->cols != wq->rows) return VQ_ERR_SHAPE;
+        if (!good_step(s_y)) return VQ_ERR_STEP;
+    }
+    return run_linear(xq, s_x, wq, s_w, s_w_per_channel ? 1 : 0, bias, act, acc_out, y_out, s_y, yq_out,
+                      nullptr, (hipStream_t)stream, wp);
 }
 
 vq_status vq_matmul_qk(const vq_qmat *q, const vq_qmat *k, int32_t B, int32_t H, int32_t N,
@@ -351,6 +401,14 @@ vq_status vq_attention_block(const vq_block_desc *d, const vq_qmat *xq, int64_t 
     if (((uintptr_t)y_out) % 16 != 0) return VQ_ERR_STRIDE;
     for (void *dp : {d->dump_qkv, d->dump_o, d->dump_x2, d->dump_h})
         if (((uintptr_t)dp) % 16 != 0) return VQ_ERR_STRIDE;
+    {
+        const int have = (d->wp_qkv != nullptr) + (d->wp_proj != nullptr) + (d->wp_fc1 != nullptr) +
+                         (d->wp_fc2 != nullptr);
+        if (have != 0 && have != (d->hidden ? 4 : 2)) return VQ_ERR_NULL;
+        if (have != 0 && (!d->wp_qkv || !d->wp_proj)) return VQ_ERR_NULL;
+        for (const void *wp : {d->wp_qkv, d->wp_proj, d->wp_fc1, d->wp_fc2})
+            if (((uintptr_t)wp) % 16 != 0) return VQ_ERR_STRIDE;
+    }
 
     uint8_t *ws = (uint8_t *)workspace;
     uint8_t *qkv = d->dump_qkv ? (uint8_t *)d->dump_qkv : ws + L.qkv_off;
@@ -371,7 +429,7 @@ vq_status vq_attention_block(const vq_block_desc *d, const vq_qmat *xq, int64_t 
     ex.head_major = 1; ex.D = d->D; ex.dh = 64; ex.Ntok = d->N; ex.Bimg = (int)B; ex.Hh = d->H;
     ex.s_q = d->s_q; ex.s_k = d->s_k; ex.s_v = d->s_v; ex.dst = qkv; ex.sb = L.sa; ex.bits = d->bits_a;
     st = run_linear(xq, d->s_x, &d->w_qkv, d->sw_qkv, 1, d->b_qkv, 0, nullptr, nullptr, 0.0f, nullptr, &ex,
-                    stream);
+                    stream, d->wp_qkv);
     if (st != VQ_OK) return st;
     mark();
 
@@ -399,7 +457,7 @@ vq_status vq_attention_block(const vq_block_desc *d, const vq_qmat *xq, int64_t 
     // 3. projection (fp32 out, or requantized for the MLP)
     if (!d->hidden) {
         st = run_linear(&oq, d->s_o, &d->w_proj, d->sw_proj, 1, d->b_proj, 0, nullptr, y_out, 0.0f, nullptr,
-                        nullptr, stream);
+                        nullptr, stream, d->wp_proj);
         mark();
         return st;
     }
@@ -407,7 +465,7 @@ vq_status vq_attention_block(const vq_block_desc *d, const vq_qmat *xq, int64_t 
     x2.data = x2buf; x2.bits = d->bits_a; x2.storage_bits = L.sa; x2.rows = L.M; x2.cols = d->D;
     x2.row_stride = L.act_row;
     st = run_linear(&oq, d->s_o, &d->w_proj, d->sw_proj, 1, d->b_proj, 0, nullptr, nullptr, d->s_x2, &x2, nullptr,
-                    stream);
+                    stream, d->wp_proj);
     if (st != VQ_OK) return st;
     mark();
     // 4. fc1 + GELU + requant, 5. fc2
@@ -415,11 +473,11 @@ vq_status vq_attention_block(const vq_block_desc *d, const vq_qmat *xq, int64_t 
     hq.data = hbuf; hq.bits = d->bits_a; hq.storage_bits = L.sa; hq.rows = L.M; hq.cols = d->hidden;
     hq.row_stride = L.h_row;
     st = run_linear(&x2, d->s_x2, &d->w_fc1, d->sw_fc1, 1, d->b_fc1, 1, nullptr, nullptr, d->s_h, &hq, nullptr,
-                    stream);
+                    stream, d->wp_fc1);
     if (st != VQ_OK) return st;
     mark();
     st = run_linear(&hq, d->s_h, &d->w_fc2, d->sw_fc2, 1, d->b_fc2, 0, nullptr, y_out, 0.0f, nullptr, nullptr,
-                    stream);
+                    stream, d->wp_fc2);
     mark();
     return st;
 }

@@ -25,9 +25,10 @@ namespace vitq {
 
 namespace {
 
-#ifndef VITQ_S
-#define VITQ_S 3
-#define VITQ_OCC 3
+#ifndef VITQ_BK84
+#define VITQ_BK84 128
+#define VITQ_S84 2
+#define VITQ_OCC84 3
 #endif
 enum Epi { kEpiGeneric = 0, kEpiF32 = 1, kEpiQuant = 2, kEpiQuantGelu = 3 };
 
@@ -39,7 +40,8 @@ __device__ __forceinline__ int slot_of_channel(int c) {
 
 template <int WB, int AB>
 struct Shift {
-    static constexpr int value = (WB == 4 && AB == 4) ? 8 : (WB == 2 && AB == 4) ? 10 : 0;
+    // (8,4): weights expanded to plain int8 beforehand, activations unpacked to 16*x
+    static constexpr int value = (WB == 4 && AB == 4) ? 8 : (WB == 2 && AB == 4) ? 10 : (WB == 8 && AB == 4) ? 4 : 0;
 };
 
 template <int SB>
@@ -55,29 +57,40 @@ __device__ __forceinline__ void store_packed16(uint8_t *dst, const int (&q)[16])
     }
 }
 
-// Destination of this lane's 16 packed levels; nullptr if nothing is to be stored.
-// Head-major mode: channel -> (q/k/v, head, d), token -> (image, n).  The two divisions are
-// done without the integer-division expansion: the channel one by comparisons (3D channels) and
-// a shift when the head size is a power of two; the token one by an fp32 reciprocal with a
-// one-step correction (exact for m < 2^22).
-__device__ __forceinline__ uint8_t *packed_dst(const GemmParams &p, int m, int cb, int &which) {
+// Destination of a lane's 16 packed levels = yq + token part + channel part (the address is
+// linear in both).  Head-major mode: channel -> (q/k/v, head, d), token -> (image, n).  The two
+// divisions avoid the integer-division expansion: the channel one by comparisons (3D channels)
+// and a shift when the head size is a power of two; the token one by an fp32 reciprocal with a
+// one-step correction (exact for m < 2^22).  A negative part marks "nothing to store".
+__device__ __forceinline__ int64_t packed_token_part(const GemmParams &p, int m) {
+    if (m >= p.M) return -1;
+    if (p.head_major) {
+        int b = (int)((float)m * p.inv_ntok);
+        int n = m - b * p.Ntok;
+        if (n < 0) { b -= 1; n += p.Ntok; }
+        if (n >= p.Ntok) { b += 1; n -= p.Ntok; }
+        return ((int64_t)b * p.Hh * p.Ntok + n) * p.yq_stride;
+    }
+    return (int64_t)m * p.yq_stride;
+}
+__device__ __forceinline__ int64_t packed_channel_part(const GemmParams &p, int cb, int &which) {
     which = 0;
     if (p.head_major) {
-        if (cb >= p.Nout) return nullptr;
+        if (cb >= p.Nout) return -1;
         which = (cb >= p.D ? 1 : 0) + (cb >= 2 * p.D ? 1 : 0);
         const int rem = cb - which * p.D;
         int h, d;
         if (p.dh_shift >= 0) { h = rem >> p.dh_shift; d = rem & (p.dh - 1); }
         else { h = rem / p.dh; d = rem - h * p.dh; }
-        int b = (int)((float)m * p.inv_ntok);
-        int n = m - b * p.Ntok;
-        if (n < 0) { b -= 1; n += p.Ntok; }
-        if (n >= p.Ntok) { b += 1; n -= p.Ntok; }
-        const int64_t row = (((int64_t)which * p.Bimg + b) * p.Hh + h) * p.Ntok + n;
-        return p.yq + row * p.yq_stride + ((d * p.yq_sb) >> 3);
+        return (((int64_t)which * p.Bimg * p.Hh + h) * p.Ntok) * p.yq_stride + ((d * p.yq_sb) >> 3);
     }
-    if (((cb * p.yq_sb) >> 3) >= p.yq_row_bytes16) return nullptr;
-    return p.yq + (int64_t)m * p.yq_stride + ((cb * p.yq_sb) >> 3);
+    if (((cb * p.yq_sb) >> 3) >= p.yq_row_bytes16) return -1;
+    return (cb * p.yq_sb) >> 3;
+}
+__device__ __forceinline__ uint8_t *packed_dst(const GemmParams &p, int m, int cb, int &which) {
+    const int64_t t = packed_token_part(p, m), c = packed_channel_part(p, cb, which);
+    if (t < 0 || c < 0) return nullptr;
+    return p.yq + t + c;
 }
 
 // ---- exact epilogue: every output kind, the definition's operation sequence ------------------
@@ -173,27 +186,25 @@ __device__ __forceinline__ void epilogue_f32(const GemmParams &p, const v16i &ac
 // exactly.  For GELU the cheap activation (hardware exp2 / rcp) is within
 // 2^-18 * |y| * max(1,|y|) of the definition's, which widens the guard per element.
 template <bool GELU>
-__device__ __forceinline__ void epilogue_quant(const GemmParams &p, const v16i &acc, int shift, int m,
-                                               int cb, const float (&scs)[16], const float (&bs)[16],
-                                               bool force_exact) {
-    if (m >= p.M) return;
-    int which;
-    uint8_t *dst = packed_dst(p, m, cb, which);
+__device__ __forceinline__ void epilogue_quant(const GemmParams &p, const v16i &acc, int shift, uint8_t *dst,
+                                               float s_y, float r_y, int cb, const float (&scs)[16],
+                                               const float (&bs)[16], bool force_exact) {
     if (!dst) return;
-    const float sy0 = p.s_y[0], sy1 = p.s_y[1], sy2 = p.s_y[2];
-    const float ry0 = p.r_y[0], ry1 = p.r_y[1], ry2 = p.r_y[2];
-    const float s_y = which == 0 ? sy0 : (which == 1 ? sy1 : sy2);
-    const float r_y = which == 0 ? ry0 : (which == 1 ? ry1 : ry2);
     const float bias8 = -p.qminf;
     const float top = p.qmaxf - p.qminf;
     const float thr0 = 0.5f - p.eps0;
     const float gguard = p.gelu_guard * r_y;
     float lv[16];
-    bool risky = force_exact;
+    // worst = max over the elements of (distance to the nearest integer + that element's guard),
+    // taken on the bit patterns: the values are >= +0, where unsigned order is float order and
+    // a NaN compares above everything (so it is caught, which a float max would drop)
+    u32 worst = force_exact ? 0x7F800000u : 0u;
+    float dist[16];
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const float y = fmaf((float)acc[r], scs[r], bs[r]);        // the definition's y, exactly
-        float g = y, thr = thr0;
+        float g = y;
+        float t8, q8;
         if constexpr (GELU) {
             // 0.5*y*(1+tanh(u)) = y - y/(1 + 2^(2u*log2 e)),  2u*log2e = y*(k0 + k1*y^2)
             const float y2 = y * y;
@@ -201,13 +212,20 @@ __device__ __forceinline__ void epilogue_quant(const GemmParams &p, const v16i &
             const float X = __builtin_amdgcn_exp2f(w * y);
             const float rc = __builtin_amdgcn_rcpf(1.0f + X);
             g = fmaf(-y, rc, y);
-            thr = fmaf(-(fabsf(y) + y2), gguard, thr0);     // |y| + y^2 >= |y| * max(1, |y|)
+            t8 = fmaf(g, r_y, bias8);
+            q8 = rintf(t8);
+            dist[r] = fmaf(fabsf(y) + y2, gguard, fabsf(t8 - q8));   // |y| + y^2 >= |y| * max(1, |y|)
+        } else {
+            t8 = fmaf(g, r_y, bias8);
+            q8 = rintf(t8);
+            dist[r] = fabsf(t8 - q8);
         }
-        const float t8 = fmaf(g, r_y, bias8);
-        const float q8 = rintf(t8);
-        risky = risky || !(fabsf(t8 - q8) <= thr);
         lv[r] = __builtin_amdgcn_fmed3f(q8, 0.0f, top);
     }
+#pragma unroll
+    for (int r = 0; r < 16; r += 2)
+        worst = max(worst, max(__float_as_uint(dist[r]), __float_as_uint(dist[r + 1])));
+    const bool risky = worst > __float_as_uint(thr0);
     if (__builtin_amdgcn_ballot_w64(risky) != 0) {
         // some element of this wave's 32x32 block sits within the error bound of a rounding
         // boundary: redo the block with the definition's exact operation sequence (rare)
@@ -287,7 +305,7 @@ template <int CH>
 __device__ __forceinline__ int swz(int row) {
     if constexpr (CH == 4) return ((row >> 2) & 3) ^ (row & 2);
     else if constexpr (CH == 8) return row & 7;
-    else if constexpr (CH == 2) return (row >> 2) & 1;
+    else if constexpr (CH == 2) return (row >> 3) & 1;
     else return 0;
 }
 
@@ -296,11 +314,10 @@ __device__ __forceinline__ int channel_of_slot(int s) {
     return 16 * ((s >> 2) & 1) + 4 * (s >> 3) + (s & 3);
 }
 
-template <int WB, int AB, int TC, int TT, int WAVES_C, int WAVES_T, int BK, int EPI>
-__global__ __launch_bounds__(WAVES_C *WAVES_T * 64, VITQ_OCC)
+template <int WB, int AB, int TC, int TT, int WAVES_C, int WAVES_T, int BK, int S, int OCC, int EPI>
+__global__ __launch_bounds__(WAVES_C *WAVES_T * 64, OCC)
 void gemm_kernel(GemmParams p) {
-    constexpr int NT = WAVES_C * WAVES_T * 64;
-    constexpr int S = VITQ_S;                                      // k-stages resident in LDS
+    constexpr int NT = WAVES_C * WAVES_T * 64;                // S = k-stages resident in LDS
     constexpr int WROW = BK * WB / 8, XROW = BK * AB / 8;     // bytes per row per stage
     constexpr int WCH = WROW / 16, XCH = XROW / 16;           // 16-byte chunks per row
     constexpr int W_ITERS = TC * WCH / NT, X_ITERS = TT * XCH / NT;
@@ -543,11 +560,19 @@ void gemm_kernel(GemmParams p) {
             });
         });
     } else {
+        int64_t tok_part[NTK];
+        if constexpr (EPI == kEpiQuant || EPI == kEpiQuantGelu) {
+#pragma unroll
+            for (int ti = 0; ti < NTK; ++ti)
+                tok_part[ti] = packed_token_part(p, t0 + wave_t * WT + ti * 32 + li);
+        }
         static_for<NC>([&](auto CI) {
             constexpr int ci = decltype(CI)::value;
             const int cl = wave_c * WC + ci * 32 + 16 * g;     // channel offset inside the tile
             const int cb = c0 + cl;
             float bs[16], scs[16];
+            int64_t ch_part = -1;
+            float s_y = 1.0f, r_y = 1.0f;
             if constexpr (EPI != kEpiGeneric) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
@@ -556,22 +581,31 @@ void gemm_kernel(GemmParams p) {
                     scs[4 * j] = a.x; scs[4 * j + 1] = a.y; scs[4 * j + 2] = a.z; scs[4 * j + 3] = a.w;
                     bs[4 * j] = b.x; bs[4 * j + 1] = b.y; bs[4 * j + 2] = b.z; bs[4 * j + 3] = b.w;
                 }
+                int which;
+                ch_part = packed_channel_part(p, cb, which);
+                const float sy0 = p.s_y[0], sy1 = p.s_y[1], sy2 = p.s_y[2];
+                const float ry0 = p.r_y[0], ry1 = p.r_y[1], ry2 = p.r_y[2];
+                s_y = which == 0 ? sy0 : (which == 1 ? sy1 : sy2);
+                r_y = which == 0 ? ry0 : (which == 1 ? ry1 : ry2);
             }
             static_for<NTK>([&](auto TI) {
                 constexpr int ti = decltype(TI)::value;
-                const int m = t0 + wave_t * WT + ti * 32 + li;
-                if constexpr (EPI == kEpiQuant) epilogue_quant<false>(p, acc[ci][ti], shift, m, cb, scs, bs, !fold_ok);
-                else if constexpr (EPI == kEpiQuantGelu) epilogue_quant<true>(p, acc[ci][ti], shift, m, cb, scs, bs, !fold_ok);
-                else epilogue_generic(p, acc[ci][ti], shift, m, cb);
+                if constexpr (EPI == kEpiQuant || EPI == kEpiQuantGelu) {
+                    uint8_t *dst = (ch_part >= 0 && tok_part[ti] >= 0) ? p.yq + tok_part[ti] + ch_part : nullptr;
+                    epilogue_quant<EPI == kEpiQuantGelu>(p, acc[ci][ti], shift, dst, s_y, r_y, cb, scs, bs, !fold_ok);
+                } else {
+                    const int m = t0 + wave_t * WT + ti * 32 + li;
+                    epilogue_generic(p, acc[ci][ti], shift, m, cb);
+                }
             });
         });
     }
 }
 
-template <int WB, int AB, int TC, int TT, int WAVES_C, int WAVES_T, int BK, int EPI>
+template <int WB, int AB, int TC, int TT, int WAVES_C, int WAVES_T, int BK, int S, int OCC, int EPI>
 hipError_t launch(const GemmParams &p, hipStream_t stream) {
-    constexpr size_t lds = VITQ_S * ((size_t)TC * (BK * WB / 8) + (size_t)TT * (BK * AB / 8)) + 2 * TC * sizeof(float) + 16;
-    auto kern = gemm_kernel<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, EPI>;
+    constexpr size_t lds = S * ((size_t)TC * (BK * WB / 8) + (size_t)TT * (BK * AB / 8)) + 2 * TC * sizeof(float) + 16;
+    auto kern = gemm_kernel<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, S, OCC, EPI>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -584,13 +618,13 @@ hipError_t launch(const GemmParams &p, hipStream_t stream) {
     return hipGetLastError();
 }
 
-template <int WB, int AB, int TC, int TT, int WAVES_C, int WAVES_T, int BK>
+template <int WB, int AB, int TC, int TT, int WAVES_C, int WAVES_T, int BK, int S, int OCC>
 hipError_t launch_epi(const GemmParams &p, int epi, hipStream_t stream) {
     switch (epi) {
-        case kEpiF32: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, kEpiF32>(p, stream);
-        case kEpiQuant: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, kEpiQuant>(p, stream);
-        case kEpiQuantGelu: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, kEpiQuantGelu>(p, stream);
-        default: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, kEpiGeneric>(p, stream);
+        case kEpiF32: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, S, OCC, kEpiF32>(p, stream);
+        case kEpiQuant: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, S, OCC, kEpiQuant>(p, stream);
+        case kEpiQuantGelu: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, S, OCC, kEpiQuantGelu>(p, stream);
+        default: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, S, OCC, kEpiGeneric>(p, stream);
     }
 }
 
@@ -621,9 +655,10 @@ hipError_t gemm_launch(GemmParams p, int wb, int ab, hipStream_t stream) {
         for (int i = 0; i < 3; ++i)
             if (!(p.r_y[i] > 0x1p-100f && p.r_y[i] < 0x1p100f)) epi = (epi == kEpiF32) ? epi : kEpiGeneric;
     }
-    if (wb == 4 && ab == 4) return launch_epi<4, 4, 128, 128, 2, 2, 128>(p, epi, stream);
-    if (wb == 2 && ab == 4) return launch_epi<2, 4, 128, 128, 2, 2, 128>(p, epi, stream);
-    if (wb == 8 && ab == 8) return launch_epi<8, 8, 128, 128, 2, 2, 64>(p, epi, stream);
+    if (wb == 4 && ab == 4) return launch_epi<4, 4, 128, 128, 2, 2, 128, 3, 3>(p, epi, stream);
+    if (wb == 2 && ab == 4) return launch_epi<2, 4, 128, 128, 2, 2, 128, 3, 3>(p, epi, stream);
+    if (wb == 8 && ab == 8) return launch_epi<8, 8, 128, 128, 2, 2, 64, 3, 3>(p, epi, stream);
+    if (wb == 8 && ab == 4) return launch_epi<8, 4, 128, 128, 2, 2, VITQ_BK84, VITQ_S84, VITQ_OCC84>(p, epi, stream);
     return hipErrorInvalidValue;
 }
 

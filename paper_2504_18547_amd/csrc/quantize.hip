@@ -63,6 +63,37 @@ __global__ __launch_bounds__(256) void weight_steps_kernel(const float *w, int64
 
 }  // namespace
 
+// one thread per group of sixteen columns
+__global__ __launch_bounds__(256) void prepack_kernel(const uint8_t *w, int64_t rows, int64_t cols,
+                                                      int64_t w_stride, int sb, int8_t *out, int64_t kp) {
+    const int64_t groups = kp / 16;
+    const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (id >= rows * groups) return;
+    const int64_t r = id / groups, j = id % groups;
+    int v[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int64_t c = 16 * j + i;
+        int q = 0;
+        if (c < cols) {
+            const int64_t bit = c * sb;
+            const int field = (w[r * w_stride + (bit >> 3)] >> (bit & 7)) & ((1 << sb) - 1);
+            q = (field << (32 - sb)) >> (32 - sb);      // sign extension of the sb-bit field
+        }
+        v[i] = q;
+    }
+    const int perm[16] = {0, 2, 4, 6, 1, 3, 5, 7, 8, 10, 12, 14, 9, 11, 13, 15};
+    u32 o[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        u32 x = 0;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) x |= ((u32)v[perm[4 * d + b]] & 0xFFu) << (8 * b);
+        o[d] = x;
+    }
+    *reinterpret_cast<uint4 *>(out + r * kp + 16 * j) = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
 hipError_t quantize_launch(const QuantParams &p, hipStream_t stream) {
     const int64_t total = p.rows * (p.row_bytes16 / 4);
     if (total == 0) return hipSuccess;
@@ -80,6 +111,15 @@ hipError_t weight_steps_launch(const float *w, int64_t rows, int64_t cols, int64
     int64_t blocks = (rows + 3) / 4;
     hipLaunchKernelGGL(weight_steps_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, w, rows, cols, ld,
                        qmaxf, step_out);
+    return hipGetLastError();
+}
+
+hipError_t prepack_launch(const uint8_t *w, int64_t rows, int64_t cols, int64_t w_stride, int sb,
+                          int8_t *out, int64_t kp, hipStream_t stream) {
+    const int64_t n = rows * (kp / 16);
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(prepack_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, w, rows, cols,
+                       w_stride, sb, out, kp);
     return hipGetLastError();
 }
 

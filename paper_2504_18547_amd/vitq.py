@@ -16,7 +16,8 @@ STATUS_NAMES = ["VQ_OK", "VQ_ERR_NULL", "VQ_ERR_SHAPE", "VQ_ERR_BITS", "VQ_ERR_S
                 "VQ_ERR_UNSUPPORTED", "VQ_ERR_WORKSPACE", "VQ_ERR_HIP"]
 
 EXPORTS = ["vq_status_string", "vq_weight_steps", "vq_quantize", "vq_linear", "vq_matmul_qk",
-           "vq_matmul_pv", "vq_attention_block_workspace", "vq_attention_block"]
+           "vq_matmul_pv", "vq_attention_block_workspace", "vq_attention_block",
+           "vq_prepack_weight_bytes", "vq_prepack_weight", "vq_linear_prepacked"]
 
 
 class VitqError(RuntimeError):
@@ -44,7 +45,9 @@ class vq_block_desc(C.Structure):
                 ("s_x", C.c_float), ("s_q", C.c_float), ("s_k", C.c_float), ("s_v", C.c_float),
                 ("s_o", C.c_float), ("s_x2", C.c_float), ("s_h", C.c_float), ("scale", C.c_float),
                 ("dump_qkv", C.c_void_p), ("dump_o", C.c_void_p), ("dump_x2", C.c_void_p),
-                ("dump_h", C.c_void_p), ("stage_events", C.POINTER(C.c_void_p))]
+                ("dump_h", C.c_void_p), ("stage_events", C.POINTER(C.c_void_p)),
+                ("wp_qkv", C.c_void_p), ("wp_proj", C.c_void_p), ("wp_fc1", C.c_void_p),
+                ("wp_fc2", C.c_void_p)]
 
 
 _lib = None
@@ -72,6 +75,10 @@ def lib():
         _lib.vq_attention_block_workspace.argtypes = [C.POINTER(vq_block_desc), C.c_int64,
                                                       C.POINTER(C.c_size_t)]
         _lib.vq_attention_block.argtypes = [C.POINTER(vq_block_desc), qp, C.c_int64, vp, vp, C.c_size_t, vp]
+        _lib.vq_prepack_weight_bytes.argtypes = [qp, C.POINTER(C.c_size_t)]
+        _lib.vq_prepack_weight.argtypes = [qp, vp, C.c_size_t, vp]
+        _lib.vq_linear_prepacked.argtypes = [qp, C.c_float, qp, vp, vp, C.c_int32, vp, C.c_int32, vp, vp,
+                                             C.c_float, qp, vp]
         for n in EXPORTS[1:]:
             getattr(_lib, n).restype = C.c_int
     return _lib
@@ -153,6 +160,22 @@ def vq_linear(xq, s_x, wq, s_w, s_w_per_channel, bias, act, acc_out, y_out, s_y,
                            _ptr(acc_out), _ptr(y_out), float(s_y), _q(yq_out), _stream()), "vq_linear")
 
 
+def vq_prepack_weight(wq):
+    """Expanded int8 copy of a packed 2-/4-bit weight matrix (a new uint8 device tensor)."""
+    import torch
+    n = C.c_size_t()
+    _check(lib().vq_prepack_weight_bytes(_q(wq), C.byref(n)), "vq_prepack_weight_bytes")
+    out = torch.empty(max(n.value, 16), dtype=torch.uint8, device=wq.data.device)
+    _check(lib().vq_prepack_weight(_q(wq), _ptr(out), n.value, _stream()), "vq_prepack_weight")
+    return out
+
+
+def vq_linear_prepacked(xq, s_x, wq, wp, s_w, s_w_per_channel, bias, act, acc_out, y_out, s_y, yq_out):
+    _check(lib().vq_linear_prepacked(_q(xq), float(s_x), _q(wq), _ptr(wp), _ptr(s_w), int(s_w_per_channel),
+                                     _ptr(bias), int(act), _ptr(acc_out), _ptr(y_out), float(s_y), _q(yq_out),
+                                     _stream()), "vq_linear_prepacked")
+
+
 def vq_matmul_qk(q, k, B, H, N, s_q, s_k, scale, s_acc_out, p_out):
     _check(lib().vq_matmul_qk(_q(q), _q(k), B, H, N, float(s_q), float(s_k), float(scale), _ptr(s_acc_out),
                               _q(p_out), _stream()), "vq_matmul_qk")
@@ -179,6 +202,10 @@ def make_block_desc(dims, bits_a, bits_p, storage_a, weights, steps, dumps=None)
             setattr(d, name, float(steps[name]))
     for name, t in (dumps or {}).items():
         setattr(d, "dump_" + name, t.data_ptr())
+    for name in ("qkv", "proj", "fc1", "fc2"):
+        t = weights.get("wp_" + name)
+        if t is not None:
+            setattr(d, "wp_" + name, t.data_ptr())
     return d
 
 

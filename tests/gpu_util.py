@@ -44,10 +44,14 @@ def quantized_weights(w_fp, bits_w):
     return out
 
 
-def device_weights(wts, bits_w):
+def device_weights(wts, bits_w, prepack=False):
+    """prepack: also make the expanded int8 copies (wp_*) with vq_prepack_weight, as bench.py does."""
     out = {}
     for k, v in wts.items():
         out[k] = to_qmat(v, bits_w) if k.startswith("w_") else dev(v)
+    if prepack and storage_of(bits_w) in (2, 4):
+        for k in [k for k in out if k.startswith("w_")]:
+            out["wp_" + k[2:]] = vitq.vq_prepack_weight(out[k])
     return out
 
 

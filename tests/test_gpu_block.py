@@ -11,7 +11,7 @@ from paper_2504_18547_amd import vitq, workloads as wl
 from tests.gpu_util import assert_fp32_close, dev, device_weights, quantized_weights, storage_of
 
 
-def run_block_gpu(name, images, sharp, bits_w, bits_a, dumps=True, x_levels=None, wts=None):
+def run_block_gpu(name, images, sharp, bits_w, bits_a, dumps=True, x_levels=None, wts=None, prepack=False):
     """Returns (gpu outputs dict, oracle-side inputs) for the given images of a workload."""
     dims = wl.block_dims(name)
     D, H, N, hidden = dims["D"], dims["H"], dims["N"], dims["hidden"]
@@ -20,7 +20,7 @@ def run_block_gpu(name, images, sharp, bits_w, bits_a, dumps=True, x_levels=None
     sa = storage_of(bits_a)
     if wts is None:
         wts = quantized_weights(wl.block_weights(name, sharp=sharp), bits_w)
-    wd = device_weights(wts, bits_w)
+    wd = device_weights(wts, bits_w, prepack=prepack)
     tokens = wl.block_tokens(name, images).reshape(B * N, D)
     # the GPU quantizes its own input tokens with vq_quantize (parity-tested separately)
     xq = vitq.QMat.empty(B * N, D, bits_a)
@@ -64,10 +64,11 @@ def compare_with_oracle(out, inp, bits_a, what=""):
 
 @pytest.mark.parametrize("name", ["tiny_attn", "tiny_block"])
 @pytest.mark.parametrize("sharp", [False, True])
-@pytest.mark.parametrize("bits_w,bits_a", [(4, 4), (3, 4), (2, 4), (8, 8)])
-def test_tiny_blocks_all_bit_widths(name, sharp, bits_w, bits_a):
+@pytest.mark.parametrize("bits_w,bits_a,prepack", [(4, 4, False), (3, 4, False), (2, 4, False), (8, 8, False),
+                                                   (4, 4, True), (3, 4, True), (2, 4, True)])
+def test_tiny_blocks_all_bit_widths(name, sharp, bits_w, bits_a, prepack):
     images = list(range(wl.BLOCKS[name]["batch"]))
-    out, inp = run_block_gpu(name, images, sharp, bits_w, bits_a)
+    out, inp = run_block_gpu(name, images, sharp, bits_w, bits_a, prepack=prepack)
     ref = compare_with_oracle(out, inp, bits_a, "%s w%da%d" % (name, bits_w, bits_a))
     if sharp:
         assert len(np.unique(ref["o"])) >= 5          # the attention output is not degenerate
@@ -75,13 +76,13 @@ def test_tiny_blocks_all_bit_widths(name, sharp, bits_w, bits_a):
 
 def test_paper_head_shape_n198():
     """Table I's shape: N = 198 tokens, 384 inputs, 6 heads of 64."""
-    out, inp = run_block_gpu("deit_s_table1", [0, 1], True, 4, 4)
+    out, inp = run_block_gpu("deit_s_table1", [0, 1], True, 4, 4, prepack=True)
     compare_with_oracle(out, inp, 4, "deit_s_table1")
 
 
 def test_config2_vit_s_attention_reduced_batch():
     for sharp in (False, True):
-        out, inp = run_block_gpu("vit_s_attn", [0, 1, 2], sharp, 4, 4)
+        out, inp = run_block_gpu("vit_s_attn", [0, 1, 2], sharp, 4, 4, prepack=sharp)
         compare_with_oracle(out, inp, 4, "vit_s_attn sharp=%s" % sharp)
 
 

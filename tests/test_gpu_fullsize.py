@@ -12,14 +12,14 @@ from paper_2504_18547_amd import vitq, workloads as wl
 from tests.gpu_util import assert_fp32_close, dev, device_weights, quantized_weights, storage_of
 
 
-def _full_batch(name, sharp, bits_w, bits_a, sample):
+def _full_batch(name, sharp, bits_w, bits_a, sample, prepack=False):
     dims = wl.block_dims(name)
     D, H, N, hidden = dims["D"], dims["H"], dims["N"], dims["hidden"]
     B = wl.BLOCKS[name]["batch"]
     sa = storage_of(bits_a)
     st = wl.block_steps(name, sharp, bits_w, bits_a)
     wts = quantized_weights(wl.block_weights(name, sharp=sharp), bits_w)
-    wd = device_weights(wts, bits_w)
+    wd = device_weights(wts, bits_w, prepack=prepack)
     xq = vitq.QMat.empty(B * N, D, bits_a)
     chunk = 32
     for b0 in range(0, B, chunk):                       # stage the tokens in chunks (host memory)
@@ -51,6 +51,10 @@ def test_config4_vit_b_block_b256_w4a4(sharp):
 @pytest.mark.parametrize("bits_w,bits_a", [(3, 4), (2, 4), (8, 8)])
 def test_config4_other_bit_widths(bits_w, bits_a):
     _full_batch("vit_b_block", True, bits_w, bits_a, sample=[77, 255])
+
+
+def test_config4_expanded_weight_kernels():
+    _full_batch("vit_b_block", True, 4, 4, sample=[200], prepack=True)
 
 
 def test_config2_vit_s_attention_b64():

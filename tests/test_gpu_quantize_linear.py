@@ -52,14 +52,20 @@ def test_weight_steps_zero_row():
     assert s[0] == 1.0 and s[2] == 1.0 and s[1] == np.float32(0.21) / np.float32(7)
 
 
-def _run_linear(xq, s_x, wq, s_w, bias, bits_x, bits_w, act=0, s_y=None, bits_y=4, per_channel=True):
+def _run_linear(xq, s_x, wq, s_w, bias, bits_x, bits_w, act=0, s_y=None, bits_y=4, per_channel=True,
+                prepack=False):
     M, Nout = xq.shape[0], wq.shape[0]
     xd, wd = to_qmat(xq, bits_x), to_qmat(wq, bits_w)
     acc = torch.full((M, Nout), -7, dtype=torch.int32, device="cuda")
     y = torch.full((M, Nout), -7.0, dtype=torch.float32, device="cuda")
     yq = vitq.QMat.empty(M, Nout, bits_y) if s_y is not None else None
-    vitq.vq_linear(xd, s_x, wd, dev(s_w), int(per_channel), dev(bias), act, acc, y,
-                   0.0 if s_y is None else s_y, yq)
+    if prepack:
+        wp = vitq.vq_prepack_weight(wd)
+        vitq.vq_linear_prepacked(xd, s_x, wd, wp, dev(s_w), int(per_channel), dev(bias), act, acc, y,
+                                 0.0 if s_y is None else s_y, yq)
+    else:
+        vitq.vq_linear(xd, s_x, wd, dev(s_w), int(per_channel), dev(bias), act, acc, y,
+                       0.0 if s_y is None else s_y, yq)
     torch.cuda.synchronize()
     ref = vqo.linear(xq, s_x, wq, s_w, bias=bias, act=act, s_y=s_y, bits_y=bits_y)
     assert ref["overflow"] == 0
@@ -99,6 +105,23 @@ def test_linear_shapes_and_bit_widths(bits_x, bits_w, M, K, Nout):
     rng = np.random.default_rng(M * 7 + K + Nout + bits_w)
     xq, wq, s_w, bias = _rand_case(rng, M, K, Nout, bits_x, bits_w)
     _run_linear(xq, np.float32(0.31), wq, s_w, bias, bits_x, bits_w, s_y=np.float32(0.05), bits_y=bits_x)
+    if bits_x == 4:       # the same linear through the expanded-weight kernels
+        _run_linear(xq, np.float32(0.31), wq, s_w, bias, bits_x, bits_w, s_y=np.float32(0.05), bits_y=bits_x,
+                    prepack=True)
+
+
+def test_prepacked_weights_are_the_levels_in_operand_order():
+    rng = np.random.default_rng(91)
+    perm = [0, 2, 4, 6, 1, 3, 5, 7, 8, 10, 12, 14, 9, 11, 13, 15]
+    for bits, cols in ((4, 100), (3, 33), (2, 64), (4, 16)):
+        lo, hi = vqo.qrange(bits)
+        wq = rng.integers(lo, hi + 1, (37, cols)).astype(np.int8)
+        wp = vitq.vq_prepack_weight(to_qmat(wq, bits)).cpu().numpy().view(np.int8)
+        kp = (cols + 15) // 16 * 16
+        want = np.zeros((37, kp), np.int8)
+        want[:, :cols] = wq
+        want = want.reshape(37, kp // 16, 16)[:, :, perm].reshape(37, kp)
+        assert np.array_equal(wp[: 37 * kp].reshape(37, kp), want)
 
 
 @pytest.mark.parametrize("bits_x,bits_w", [(4, 4), (4, 2), (8, 8)])
@@ -111,6 +134,8 @@ def test_linear_extreme_operands(bits_x, bits_w):
         wq = np.full((70, K), wv, np.int8)
         ref = _run_linear(xq, np.float32(1.0), wq, np.ones(70, np.float32), None, bits_x, bits_w)
         assert ref["acc"][0, 0] == xv * wv * K
+        if bits_x == 4:
+            _run_linear(xq, np.float32(1.0), wq, np.ones(70, np.float32), None, bits_x, bits_w, prepack=True)
 
 
 def test_linear_gelu_requant_and_per_tensor_weight_step():
@@ -122,6 +147,8 @@ def test_linear_gelu_requant_and_per_tensor_weight_step():
     _run_linear(xq, np.float32(0.2), wq, s_w[:1], None, 4, 4, per_channel=False)
     _run_linear(xq, np.float32(0.2), wq, s_w, bias, 4, 4, act=1, s_y=np.float32(0.004), bits_y=8)
     _run_linear(xq, np.float32(0.2), wq, s_w, bias, 4, 4, s_y=np.float32(0.5), bits_y=2)
+    _run_linear(xq, np.float32(0.2), wq, s_w, bias, 4, 4, act=1, s_y=np.float32(0.12), bits_y=4, prepack=True)
+    _run_linear(xq, np.float32(0.2), wq, s_w, bias, 4, 4, act=1, s_y=np.float32(0.004), bits_y=8, prepack=True)
 
 
 def test_linear_only_requested_outputs_are_written_and_runs_are_deterministic():
