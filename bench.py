@@ -194,16 +194,20 @@ def main():
     gemm_ops = 2 * B * sum(macs[s] for s in lin)
     gemm_ms = sum(stage_ms[s] for s in lin)
     achieved = gemm_ops / (gemm_ms * 1e-3) / 1e12
-    traffic = None
+    # HBM bytes per GEMM launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this
+    # workload (counter passes are separate runs; see profiles/), null for other workloads
+    traffic, traffic_detail = None, None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and not args.prepack:
         with open(tpath) as f:
-            traffic = json.load(f).get("%s/w%da%d/b%d" % (name, bw, ba, B))
+            traffic_detail = json.load(f).get("%s/w%da%d/b%d" % (name, bw, ba, B))
+        if traffic_detail:
+            traffic = traffic_detail["bytes_per_launch"]
     roofline = {"kernel": "gemm_kernel<W%d,A%d> (4 launches per step: qkv, proj, fc1, fc2)" % (bw, sa),
                 "bound": "mfma", "achieved": achieved, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                 "frac": achieved / INT8_MFMA_PEAK_TOPS,
                 "avg_launch_ms": gemm_ms / len(lin), "ops_per_launch": gemm_ops / len(lin),
-                "traffic": traffic}
+                "traffic": traffic, "traffic_detail": traffic_detail}
     by = opcount.block_algorithmic_bytes(D, H, N, hidden, sa, 4 if bw == 3 else bw)
     alg_bytes = B * (by["per_image"] + N * D * 4) + by["weights"]     # + fp32 tokens read by vq_quantize
     out = {
