@@ -119,10 +119,16 @@ bool scaled_alpha(float s_q, float s_k, float scale, int shift, AttnParams *p) {
     // Exponential table for 4-bit operands: the score difference d = max - S is an integer in
     // [0, 8192].  Beyond alpha*d >= 22.5 the fixed-point value is 0 (the shift is >= 22 and the
     // mantissa is < 2^22), so the table ends there with one shared zero entry.
+    // The table is cut at kLutCap entries (filling it is per-workgroup work and it occupies LDS);
+    // with very small alpha it then ends before the exponential reaches 0, and the kernel
+    // computes the rare rows with a larger score spread directly.
     p->lut_n = 0;
+    p->lut_full = 1;
     if (shift == 8) {
+        const int kLutCap = 2048;
         double need = 22.5 / (double)alpha + 2.0;
         int n = need > 8193.0 ? 8193 : (int)need;
+        if (n > kLutCap) { n = kLutCap; p->lut_full = 0; }
         p->lut_n = n + 1;
     }
     return true;

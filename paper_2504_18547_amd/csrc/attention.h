@@ -18,6 +18,9 @@ struct AttnParams {
     float alpha_scaled;          // ((s_q*s_k)*scale)*log2(e), divided by the operand scale 2^8 at 4 bits
     float alpha;                 // the same, unscaled (fills the exponential table)
     int lut_n;                   // entries of the exponential table (0: compute directly)
+    int lut_full;                // 1: the table reaches the point where the exponential is 0 (its last
+                                 // entry stands for every larger difference); 0: it was cut short, and
+                                 // rows whose score spread exceeds it are computed directly
     int pmax;                    // 2^bits_p - 1
     // P as an input (PV-only) or output (QK-only), packed unsigned [B*H*N x N]
     const uint8_t *p_in; int64_t p_in_stride; int p_in_row_bytes16;

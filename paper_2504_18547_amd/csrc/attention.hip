@@ -30,6 +30,11 @@ __device__ __forceinline__ int vt_pos(int n) {
     return (n & ~63) + (((n & 15) >> 2) << 4) + (((n & 63) >> 4) << 2) + (n & 3);
 }
 
+// per-nibble a - b (mod 16) of eight packed nibbles, no borrows across nibbles
+__device__ __forceinline__ u32 nib_sub(u32 a, u32 b) {
+    return ((a | 0x88888888u) - (b & 0x77777777u)) ^ ((a ^ ~b) & 0x88888888u);
+}
+
 // (1+r) << floor(alpha*d) in 12.20 fixed point for an integer score difference d <= 0 (Eq. 4)
 __device__ __forceinline__ u32 shift_exp_fixed(int d, float alpha) {
     float tt = alpha * (float)d;
@@ -174,30 +179,57 @@ __global__ __launch_bounds__(256, (NT <= 13 ? 2 : 1)) void attention_kernel(Attn
             // ---- shift-based exponential in 12.20 fixed point (Eq. 4), integer row sum -------
             // e depends only on the integer difference d = max - S, so at 4 bits (d <= 8192) it is
             // read from a table that this workgroup filled with the exact operation sequence.
-            auto exp_of = [&](int sv) -> u32 {
-                if constexpr (LUT) {
-                    const int idx = min((mx - sv) >> SHIFT, lut_last);
-                    return sLUT[idx];
-                } else {
-                    return shift_exp_fixed(sv - mx, p.alpha_scaled);
+            bool direct = !LUT;
+            if constexpr (LUT) {
+                if (!p.lut_full) {
+                    // cut table: a row whose spread max - min reaches past it cannot use it
+                    int mn = INT32_MAX;
+                    static_for<NT>([&](auto T) {
+                        constexpr int t = decltype(T)::value;
+                        if (TAIL && t < NT - 1) {
+                            mn = min(mn, min(min(s[t][0], s[t][1]), min(s[t][2], s[t][3])));
+                        } else {
+#pragma unroll
+                            for (int r = 0; r < 4; ++r)
+                                if (16 * t + 4 * g + r < N) mn = min(mn, s[t][r]);
+                        }
+                    });
+                    mn = min(mn, __shfl_xor(mn, 16, 64));
+                    mn = min(mn, __shfl_xor(mn, 32, 64));
+                    direct = __builtin_amdgcn_ballot_w64(((mx - mn) >> SHIFT) >= lut_last) != 0;
                 }
-            };
+            }
             u32 sum = 0;
-            static_for<NT>([&](auto T) {
-                constexpr int t = decltype(T)::value;
-                if (TAIL && t < NT - 1) {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) { const u32 e = exp_of(s[t][r]); s[t][r] = (int)e; sum += e; }
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        u32 e = 0;
-                        if (16 * t + 4 * g + r < N) e = exp_of(s[t][r]);
-                        s[t][r] = (int)e;
-                        sum += e;
+            auto exp_pass = [&](auto DIRECT) {
+                auto exp_of = [&](int sv) -> u32 {
+                    if constexpr (LUT && !decltype(DIRECT)::value) {
+                        // scores carry the operand factor 2^SHIFT, so (mx - sv) >> (SHIFT - 2) is the
+                        // byte offset 4*d of entry d directly
+                        constexpr int LSH = SHIFT >= 2 ? SHIFT - 2 : 0;     // (the table exists at 4 bits only)
+                        const u32 off = min((u32)(mx - sv) >> LSH, 4u * (u32)lut_last);
+                        return *reinterpret_cast<const u32 *>(reinterpret_cast<const uint8_t *>(sLUT) + off);
+                    } else {
+                        return shift_exp_fixed(sv - mx, p.alpha_scaled);
                     }
-                }
-            });
+                };
+                static_for<NT>([&](auto T) {
+                    constexpr int t = decltype(T)::value;
+                    if (TAIL && t < NT - 1) {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) { const u32 e = exp_of(s[t][r]); s[t][r] = (int)e; sum += e; }
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            u32 e = 0;
+                            if (16 * t + 4 * g + r < N) e = exp_of(s[t][r]);
+                            s[t][r] = (int)e;
+                            sum += e;
+                        }
+                    }
+                });
+            };
+            if (direct) exp_pass(std::true_type{});
+            else exp_pass(std::false_type{});
             sum += __shfl_xor(sum, 16, 64);
             sum += __shfl_xor(sum, 32, 64);
             // ---- P level = #{k : 2*pmax*e > (2k-1)*sum} (division absorbed into the comparator) --
@@ -302,7 +334,7 @@ __global__ __launch_bounds__(256, (NT <= 13 ? 2 : 1)) void attention_kernel(Attn
                 }
             }
             if (qok) {
-                int q16[16];
+                float lv[16];            // level - qmin, in [0, qmax - qmin]
                 float of[16];
                 int oa[16];
                 // requantization: cheap value fma(o, 1/s_o, -qmin) with the same guard as the
@@ -310,7 +342,7 @@ __global__ __launch_bounds__(256, (NT <= 13 ? 2 : 1)) void attention_kernel(Attn
                 // with the exact division
                 const float bias8 = -p.qminf, top = p.qmaxf - p.qminf;
                 const float thr_o = 0.5f - p.eps_o;
-                bool risky_o = false;
+                u32 worst_o = 0u;        // max distance to the rounded value, as bit patterns (NaN on top)
 #pragma unroll
                 for (int T = 0; T < 4; ++T)
 #pragma unroll
@@ -322,12 +354,13 @@ __global__ __launch_bounds__(256, (NT <= 13 ? 2 : 1)) void attention_kernel(Attn
                         of[4 * T + r] = ov;
                         const float t8 = fmaf(ov, p.r_o, bias8);
                         const float q8 = rintf(t8);
-                        risky_o = risky_o || !(fabsf(t8 - q8) <= thr_o);
-                        q16[4 * T + r] = (int)__builtin_amdgcn_fmed3f(q8, 0.0f, top) + (int)p.qminf;
+                        worst_o = max(worst_o, __float_as_uint(fabsf(t8 - q8)));
+                        lv[4 * T + r] = __builtin_amdgcn_fmed3f(q8, 0.0f, top);
                     }
-                if (__builtin_amdgcn_ballot_w64(risky_o) != 0) {
+                if (__builtin_amdgcn_ballot_w64(worst_o > __float_as_uint(thr_o)) != 0) {
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) q16[i] = quantize_level(of[i], p.s_o, p.qminf, p.qmaxf);
+                    for (int i = 0; i < 16; ++i)
+                        lv[i] = __builtin_amdgcn_fmed3f(rintf(of[i] / p.s_o) + bias8, 0.0f, top);
                 }
                 const int d0 = 16 * g;
                 if (p.o_acc_out) {
@@ -343,12 +376,34 @@ __global__ __launch_bounds__(256, (NT <= 13 ? 2 : 1)) void attention_kernel(Attn
                 }
                 if (p.oq) {
                     uint8_t *dst = p.oq + orow * p.oq_stride + (((h * 64 + d0) * p.oq_sb) >> 3);
-                    u32 w[4];
                     if (p.oq_sb == 4) {
-                        pack16<4>(q16, w);
-                        *reinterpret_cast<uint2 *>(dst) = make_uint2(w[0], w[1]);
+                        // even-indexed levels in the low nibbles of one word, odd-indexed shifted into
+                        // the high ones; the stored levels are biased by -qmin = 8, and flipping bit 3
+                        // turns them into two's complement
+                        u32 ev0 = 0, od0 = 0, ev1 = 0, od1 = 0;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            ev0 = __builtin_amdgcn_cvt_pk_u8_f32(lv[2 * i], i, ev0);
+                            od0 = __builtin_amdgcn_cvt_pk_u8_f32(lv[2 * i + 1], i, od0);
+                            ev1 = __builtin_amdgcn_cvt_pk_u8_f32(lv[8 + 2 * i], i, ev1);
+                            od1 = __builtin_amdgcn_cvt_pk_u8_f32(lv[8 + 2 * i + 1], i, od1);
+                        }
+                        const u32 fix = 0x11111111u * ((u32)bias8 & 0xFu);
+                        // per-nibble subtraction of the bias (a power of two: 2^(bits-1)) modulo 16
+                        const u32 w0 = nib_sub(ev0 | (od0 << 4), fix);
+                        const u32 w1 = nib_sub(ev1 | (od1 << 4), fix);
+                        *reinterpret_cast<uint2 *>(dst) = make_uint2(w0, w1);
                     } else {
-                        pack16<8>(q16, w);
+                        const u32 fix = 0x01010101u * ((u32)bias8 & 0xFFu);
+                        u32 w[4];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            u32 v = 0;
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) v = __builtin_amdgcn_cvt_pk_u8_f32(lv[4 * j + i], i, v);
+                            // per-byte subtraction of the bias without borrows across bytes
+                            w[j] = ((v | 0x80808080u) - (fix & 0x7F7F7F7Fu)) ^ ((v ^ ~fix) & 0x80808080u);
+                        }
                         *reinterpret_cast<uint4 *>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
                     }
                 }

@@ -249,9 +249,12 @@ __device__ __forceinline__ void epilogue_quant(const GemmParams &p, const v16i &
             ev1 = __builtin_amdgcn_cvt_pk_u8_f32(lv[8 + 2 * i], i, ev1);
             od1 = __builtin_amdgcn_cvt_pk_u8_f32(lv[8 + 2 * i + 1], i, od1);
         }
-        // stored levels are biased by -qmin = 8; flipping bit 3 turns them into two's complement
-        const u32 w0 = (ev0 | (od0 << 4)) ^ 0x88888888u;
-        const u32 w1 = (ev1 | (od1 << 4)) ^ 0x88888888u;
+        // stored levels are biased by -qmin = 2^(bits-1); remove it per nibble, modulo 16 and
+        // without borrows across nibbles (for 4-bit levels this is a flip of bit 3)
+        const u32 fix = 0x11111111u * ((u32)bias8 & 0xFu);
+        const u32 a0 = ev0 | (od0 << 4), a1 = ev1 | (od1 << 4);
+        const u32 w0 = ((a0 | 0x88888888u) - (fix & 0x77777777u)) ^ ((a0 ^ ~fix) & 0x88888888u);
+        const u32 w1 = ((a1 | 0x88888888u) - (fix & 0x77777777u)) ^ ((a1 ^ ~fix) & 0x88888888u);
         *reinterpret_cast<uint2 *>(dst) = make_uint2(w0, w1);
     } else {
         // 8-bit storage: the bias -qmin = 2^(bits-1) is removed modulo 256

@@ -109,6 +109,11 @@ def row_stride_for(cols, storage_bits):
     return ((cols * storage_bits + 7) // 8 + 15) // 16 * 16
 
 
+def default_storage(bits):
+    """Smallest storage field (2, 4 or 8 bits) that holds b-bit levels."""
+    return 2 if bits <= 2 else (4 if bits <= 4 else 8)
+
+
 class QMat:
     """A packed quantized matrix: a uint8 tensor [rows, row_stride] plus its description."""
 
@@ -118,12 +123,12 @@ class QMat:
         self.rows, self.row_stride = data.shape
         self.cols = int(cols)
         self.bits = int(bits)
-        self.storage_bits = int(storage_bits if storage_bits is not None else (4 if bits == 3 else bits))
+        self.storage_bits = int(storage_bits if storage_bits is not None else default_storage(bits))
         self.unsigned = bool(unsigned)
 
     @staticmethod
     def empty(rows, cols, bits, storage_bits=None, unsigned=False, device="cuda", row_stride=None):
-        sb = storage_bits if storage_bits is not None else (4 if bits == 3 else bits)
+        sb = storage_bits if storage_bits is not None else default_storage(bits)
         stride = row_stride if row_stride is not None else row_stride_for(cols, sb)
         return QMat(torch.zeros((rows, stride), dtype=torch.uint8, device=device), cols, bits, sb, unsigned)
 

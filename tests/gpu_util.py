@@ -12,7 +12,8 @@ from paper_2504_18547_amd import vitq
 
 
 def storage_of(bits):
-    return 4 if bits == 3 else bits
+    """Smallest storage field (2, 4 or 8 bits) that holds b-bit levels."""
+    return 2 if bits <= 2 else (4 if bits <= 4 else 8)
 
 
 def to_qmat(levels, bits, storage_bits=None, row_stride=None):

@@ -72,16 +72,35 @@ def test_qk_extremes_ties_and_uniform_rows():
     assert ref["p"][0, 0, 0, 50] == 15 and ref["p"][0, 0, 0].sum() == 15
 
 
-def _check_pv(p, v, s_p, s_v, s_o, bits, bits_p, p_storage=None):
+def test_qk_small_alpha_rows_beyond_the_exponential_table():
+    """With small steps the exponential has not reached 0 where the kernel's table ends: rows whose
+    score spread exceeds the table are computed directly, the others read it."""
+    rng = np.random.default_rng(321)
+    for N in (5, 24):
+        q, k, _ = _heads(rng, 2, 2, N, 4, spread=0.5)  # spreads of a few hundred: inside the table
+        q[0, 0, 1, :] = 7
+        k[0, 0, 2, :] = 7
+        k[0, 0, 3, :] = -8                              # row 1 of head (0,0): spread 64*7*15 = 6720
+        q[1, 1, 4, :] = -8
+        k[1, 1, 0, :] = -8
+        k[1, 1, N - 1, :] = 7                           # spread 64*8*15 = 7680
+        ref = _check_qk(q, k, np.float32(0.2), np.float32(0.2), 4, 4)
+        spread = ref["s_acc"].max(axis=-1) - ref["s_acc"].min(axis=-1)
+        assert (spread >= 2048).sum() >= 2 and (spread < 2048).sum() >= 2 * N
+        assert len(np.unique(ref["p"])) >= 3
+
+
+def _check_pv(p, v, s_p, s_v, s_o, bits, bits_p, p_storage=None, bits_o=None):
     B, H, N, _ = v.shape
     pd = to_qmat(p.reshape(-1, N), bits_p, storage_bits=p_storage)
     vd = to_qmat(v.reshape(-1, 64), bits)
     o_acc = torch.full((B * H * N, 64), -9, dtype=torch.int32, device="cuda")
     o = torch.full((B * N, H * 64), -9.0, dtype=torch.float32, device="cuda")
-    oq = vitq.QMat.empty(B * N, H * 64, bits)
+    bits_o = bits if bits_o is None else bits_o
+    oq = vitq.QMat.empty(B * N, H * 64, bits_o, storage_bits=bits)
     vitq.vq_matmul_pv(pd, vd, B, H, N, s_p, s_v, o_acc, o, s_o, oq)
     torch.cuda.synchronize()
-    ref = vqo.matmul_pv(p, v, s_p, s_v, s_o=s_o, bits_o=bits)
+    ref = vqo.matmul_pv(p, v, s_p, s_v, s_o=s_o, bits_o=bits_o)
     assert np.array_equal(o_acc.cpu().numpy().reshape(B, H, N, 64), ref["o_acc"]), "accumulators differ"
     assert_fp32_close(o.cpu().numpy(), ref["o"], "o")
     assert np.array_equal(from_qmat(oq), ref["oq"]), "requantized O differs"
@@ -108,6 +127,18 @@ def test_pv_8bit_levels(N):
     _check_pv(p, v, np.float32(1) / np.float32(255), np.float32(0.02), np.float32(0.7), 8, 8)
     p4 = (p >> 4).astype(np.uint8)
     _check_pv(p4, v, np.float32(1) / np.float32(15), np.float32(0.02), np.float32(0.7), 8, 4, p_storage=8)
+
+
+@pytest.mark.parametrize("bits,bits_o", [(4, 3), (4, 2), (8, 5), (8, 7)])
+def test_pv_output_levels_narrower_than_their_storage(bits, bits_o):
+    rng = np.random.default_rng(500 + bits_o)
+    _, _, v = _heads(rng, 1, 2, 100, bits)
+    p = rng.integers(0, 16, (1, 2, 100, 100)).astype(np.uint8)
+    s_v = np.float32(0.4 if bits == 4 else 0.02)
+    ref = _check_pv(p, v, np.float32(1) / np.float32(15), s_v, np.float32(6.0 / (1 << bits_o)), bits, 4,
+                    p_storage=bits, bits_o=bits_o)
+    lo, hi = vqo.qrange(bits_o)
+    assert ref["oq"].min() == lo and ref["oq"].max() == hi
 
 
 def test_pv_one_hot_rows_and_extremes():

@@ -151,6 +151,20 @@ def test_linear_gelu_requant_and_per_tensor_weight_step():
     _run_linear(xq, np.float32(0.2), wq, s_w, bias, 4, 4, act=1, s_y=np.float32(0.004), bits_y=8, prepack=True)
 
 
+@pytest.mark.parametrize("bits_y", [2, 3, 4, 5, 7, 8])
+def test_linear_requant_to_every_level_count(bits_y):
+    """Levels narrower than their storage field (3 bits in a nibble, 5..7 in a byte) take the same epilogues."""
+    rng = np.random.default_rng(300 + bits_y)
+    xq, wq, s_w, bias = _rand_case(rng, 130, 192, 160, 4, 4)
+    s_w = (s_w * 40).astype(np.float32)
+    s_y = np.float32(1.2 / (1 << (bits_y - 1)))
+    for act in (0, 1):
+        ref = _run_linear(xq, np.float32(0.2), wq, s_w, bias, 4, 4, act=act, s_y=s_y, bits_y=bits_y)
+        lo, hi = vqo.qrange(bits_y)
+        assert ref["yq"].min() == lo or act == 1
+        assert ref["yq"].max() == hi
+
+
 def test_linear_only_requested_outputs_are_written_and_runs_are_deterministic():
     rng = np.random.default_rng(56)
     xq, wq, s_w, bias = _rand_case(rng, 197, 384, 384, 4, 4)
