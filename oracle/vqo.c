@@ -24,6 +24,7 @@
  *   shift-based exponential ............ Eq. 4
  *   row-sum-scaled comparator .......... Sec. IV-B, Fig. 4 caption
  *   P.V with scales absorbed ........... Sec. IV-B (weighted sum of values)
+ *   LayerNorm + comparator quantizer ... Sec. IV-C, Eq. 5, Fig. 5
  * Where the paper is silent the reading taken is stated at the function.
  *
  * Parity pins: every function below is pinned by tests/test_oracle_*.py
@@ -556,6 +557,100 @@ void vqo_x_softmax_true(const int32_t *s, int64_t n, double a, int pmax, uint8_t
         double lv = floor(pr * (double)pmax + 0.5);
         if (lv > (double)pmax) lv = (double)pmax;
         p[j] = (uint8_t)lv;
+    }
+}
+
+/* ------------------------------------------------------------------------ */
+/* LayerNorm followed by a quantizer, without division by sigma and without    */
+/* square root (Sec. IV-C, Eq. 5, Fig. 5).                                     */
+/*                                                                            */
+/* Row statistics: the incremental recurrences of Eq. 5 in fp32, elements in   */
+/* order i = 1..n, mu_0 = 0, M_0 = 0:                                          */
+/*     d1 = x_i - mu;  mu = mu + d1 / (float)i;  d2 = x_i - mu;                */
+/*     M  = M + d1 * d2            (a multiply, then an add)                   */
+/* M_n is the SUM of squared deviations (Eq. 5 has no 1/i in its second line), */
+/* so variance = M_n / n; the n is folded into the comparison below.           */
+/* An optional eps (reading: the usual LayerNorm stabiliser, which the paper   */
+/* does not mention; 0 switches it off) enters as V = M_n + (float)n * eps.    */
+/*                                                                            */
+/* Quantizer: level = qmin + #{k = qmin+1 .. qmax : y_j > (k - 1/2) * step}     */
+/* with y_j = (x_j - mu) / sigma * gamma_j + beta_j, decided in the comparator  */
+/* form of Fig. 5(b): both sides are multiplied by sigma > 0 and squared with   */
+/* the sign kept (the "sign logic"), ssq(v) = v * |v|:                          */
+/*     a = x_j - mu;  g = a * gamma_j;  L = (g * |g|) * (float)n               */
+/*     r = ((float)k - 0.5f) * step;  c = r - beta_j;  R = (c * |c|) * V        */
+/*     y_j > r   <=>   L > R                                                   */
+/* Reading: Fig. 5(b) scales the REFERENCE by 1/gamma; here the data side is    */
+/* scaled by gamma instead, which needs no reciprocal and stays valid for       */
+/* gamma <= 0.  A row with V == 0 (constant row, eps == 0) has no defined       */
+/* normalisation; every comparison is then "0 > +-0" = false and the row gets   */
+/* qmin.  With a residual input the element is first x_j = x_j + res_j (fp32),  */
+/* optionally returned in sum_out.                                              */
+/* Outputs: q [rows x cols] levels; mu_out, m2_out [rows] (nullable).           */
+/* ------------------------------------------------------------------------ */
+int vqo_layernorm_quantize(const float *x, const float *res, float *sum_out, int64_t rows,
+                           int64_t cols, int64_t ld, const float *gamma, const float *beta,
+                           float eps, float step, int bits, int8_t *q, float *mu_out,
+                           float *m2_out)
+{
+    int qmin, qmax;
+    if (vqo_qrange(bits, 0, &qmin, &qmax)) return 1;
+    float *row = (float *)malloc((size_t)(cols > 0 ? cols : 1) * sizeof(float));
+    if (!row) return 2;
+    for (int64_t r_ = 0; r_ < rows; ++r_) {
+        for (int64_t j = 0; j < cols; ++j) {
+            float v = x[r_ * ld + j];
+            if (res) v = v + res[r_ * ld + j];
+            row[j] = v;
+            if (sum_out) sum_out[r_ * ld + j] = v;
+        }
+        float mu = 0.0f, m2 = 0.0f;
+        for (int64_t i = 1; i <= cols; ++i) {
+            float xi = row[i - 1];
+            float d1 = xi - mu;
+            mu = mu + d1 / (float)i;
+            float d2 = xi - mu;
+            float pr = d1 * d2;
+            m2 = m2 + pr;
+        }
+        if (mu_out) mu_out[r_] = mu;
+        if (m2_out) m2_out[r_] = m2;
+        float nf = (float)cols;
+        float ne = nf * eps;
+        float V = m2 + ne;
+        for (int64_t j = 0; j < cols; ++j) {
+            float a = row[j] - mu;
+            float g = a * gamma[j];
+            float gs = g * fabsf(g);
+            float L = gs * nf;
+            int level = qmin;
+            for (int k = qmin + 1; k <= qmax; ++k) {
+                float rk = ((float)k - 0.5f) * step;
+                float c = rk - beta[j];
+                float cs = c * fabsf(c);
+                float R = cs * V;
+                if (L > R) level += 1;
+            }
+            q[r_ * cols + j] = (int8_t)level;
+        }
+    }
+    free(row);
+    return 0;
+}
+
+/* Cross-check: the direct form of Fig. 5(a) in double -- two-pass mean and    */
+/* variance, y = (x - mean) / sqrt(var + eps) * gamma + beta -- returned as y.  */
+void vqo_x_layernorm(const float *x, int64_t rows, int64_t cols, int64_t ld, const float *gamma,
+                     const float *beta, double eps, double *y)
+{
+    for (int64_t r_ = 0; r_ < rows; ++r_) {
+        double m = 0.0, v = 0.0;
+        for (int64_t j = 0; j < cols; ++j) m += (double)x[r_ * ld + j];
+        m /= (double)cols;
+        for (int64_t j = 0; j < cols; ++j) { double d = (double)x[r_ * ld + j] - m; v += d * d; }
+        v /= (double)cols;
+        for (int64_t j = 0; j < cols; ++j)
+            y[r_ * cols + j] = ((double)x[r_ * ld + j] - m) / sqrt(v + eps) * (double)gamma[j] + (double)beta[j];
     }
 }
 

@@ -341,3 +341,29 @@ def linear_dequant_first(xq, s_x, wq, s_w, bias=None):
 
 def num_threads():
     return lib().vqo_num_threads()
+
+
+def layernorm_quantize(x, gamma, beta, eps, step, bits, res=None, want_sum=False):
+    """Returns dict(q int8 [rows, cols], mu, m2 [rows], sum (x + res) if asked)."""
+    x = _c(x, np.float32)
+    rows, cols = x.shape
+    gamma, beta = _c(gamma, np.float32), _c(beta, np.float32)
+    res = None if res is None else _c(res, np.float32)
+    q = np.empty((rows, cols), np.int8)
+    mu, m2 = np.empty(rows, np.float32), np.empty(rows, np.float32)
+    total = np.empty((rows, cols), np.float32) if want_sum else None
+    rc = lib().vqo_layernorm_quantize(_ptr(x), _ptr(res), _ptr(total), _i64(rows), _i64(cols), _i64(cols),
+                                      _ptr(gamma), _ptr(beta), _f32(eps), _f32(step), _int(bits), _ptr(q),
+                                      _ptr(mu), _ptr(m2))
+    assert rc == 0
+    return dict(q=q, mu=mu, m2=m2, sum=total)
+
+
+def x_layernorm(x, gamma, beta, eps):
+    """Cross-check: direct two-pass LayerNorm in double."""
+    x = _c(x, np.float32)
+    rows, cols = x.shape
+    y = np.empty((rows, cols), np.float64)
+    lib().vqo_x_layernorm(_ptr(x), _i64(rows), _i64(cols), _i64(cols), _ptr(_c(gamma, np.float32)),
+                          _ptr(_c(beta, np.float32)), C.c_double(eps), _ptr(y))
+    return y
