@@ -224,6 +224,23 @@ def main():
         "stage_ms": stage_ms,
         "roofline": roofline,
     }
+    # Outside the step (not part of `value`): the LayerNorm + comparator-quantizer glue kernel of
+    # Sec. IV-C on the same token matrix, timed on its own with HIP events.
+    gam = torch.ones(D, device="cuda")
+    bet = torch.zeros(D, device="cuda")
+    lq = vitq.QMat.empty(B * N, D, ba)
+    e0, e1 = hip.event(), hip.event()
+    for i in range(4):
+        if i == 1:
+            hip.record(e0, stream)
+        vitq.vq_layernorm_quantize(tokens, None, None, gam, bet, 1e-5, st["s_x"], lq)
+    hip.record(e1, stream)
+    torch.cuda.synchronize()
+    ln_ms = hip.elapsed_ms(e0, e1) / 3
+    ln_bytes = B * N * D * 4 + B * N * D * sa // 8
+    out["extra"] = {"vq_layernorm_quantize": {"ms": ln_ms, "rows": B * N, "cols": D,
+                                              "algorithmic_gbs": ln_bytes / (ln_ms * 1e-3) / 1e9,
+                                              "note": "not part of the step; fp32 in, packed levels out"}}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(name, args.sharp, bw, ba, ops_img)
     print(json.dumps(out))

@@ -191,6 +191,26 @@ vq_status vq_linear_prepacked(const vq_qmat *xq, float s_x, const vq_qmat *wq, c
                               int32_t act, int32_t *acc_out, float *y_out, float s_y,
                               const vq_qmat *yq_out, void *stream);
 
+/*
+ * LayerNorm followed by the b-bit quantizer, free of division by sigma and of square roots
+ * (Sec. IV-C: incremental statistics of Eq. 5, comparator of Fig. 5(b)); the glue between the
+ * residual stream (fp32) and the next packed operand.
+ *   t[r][c]  = x[r][c] (+ residual[r][c] when residual != NULL), fp32; written to sum_out when
+ *              sum_out != NULL (the updated residual stream)
+ *   mu, M    = Eq. 5 over c = 1..cols in this order, fp32 (M = sum of squared deviations)
+ *   out[r][c]= qmin + #{k = qmin+1..qmax : ssq((t - mu)*gamma[c]) * cols
+ *                                          > ssq((k - 1/2)*step - beta[c]) * (M + cols*eps)},
+ *              ssq(v) = v*|v|  (the comparison "normalised value > reference" multiplied by
+ *              sigma and squared with the sign kept)
+ * x, residual, sum_out: device fp32 [rows x cols], leading dimension ld (elements); gamma, beta:
+ * device fp32 [cols] (gamma may have any sign); eps >= 0 (0: none); step > 0; out: packed signed
+ * levels [rows x cols].  A row whose M + cols*eps is 0 gets qmin everywhere.
+ * Errors as elsewhere: host-side checks before the launch, outputs untouched on failure.
+ */
+vq_status vq_layernorm_quantize(const float *x, const float *residual, float *sum_out, int64_t rows,
+                                int64_t cols, int64_t ld, const float *gamma, const float *beta,
+                                float eps, float step, const vq_qmat *out, void *stream);
+
 /* Bytes of workspace vq_attention_block needs for batch B (host computation only). */
 vq_status vq_attention_block_workspace(const vq_block_desc *desc, int64_t B, size_t *bytes);
 

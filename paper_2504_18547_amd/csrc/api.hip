@@ -7,6 +7,7 @@
 #include "../../include/vitq.h"
 #include "attention.h"
 #include "gemm.h"
+#include "layernorm.h"
 #include "quantize.h"
 
 using namespace vitq;
@@ -199,6 +200,26 @@ vq_status vq_linear(const vq_qmat *xq, float s_x, const vq_qmat *wq, const float
     }
     return run_linear(xq, s_x, wq, s_w, s_w_per_channel ? 1 : 0, bias, act, acc_out, y_out, s_y, yq_out,
                       nullptr, (hipStream_t)stream);
+}
+
+vq_status vq_layernorm_quantize(const float *x, const float *residual, float *sum_out, int64_t rows,
+                                int64_t cols, int64_t ld, const float *gamma, const float *beta, float eps,
+                                float step, const vq_qmat *out, void *stream) {
+    vq_status st = check_qmat(out, 0);
+    if (st != VQ_OK) return st;
+    if (rows < 0 || cols <= 0 || ld < cols || cols > (1 << 24)) return VQ_ERR_SHAPE;
+    if (out->rows != rows || out->cols != cols) return VQ_ERR_SHAPE;
+    if (!good_step(step) || !(eps >= 0.0f) || !isfinite(eps)) return VQ_ERR_STEP;
+    if (rows == 0) return VQ_OK;
+    if (!x || !gamma || !beta) return VQ_ERR_NULL;
+    LnParams p{};
+    p.x = x; p.res = residual; p.sum_out = sum_out; p.rows = rows; p.cols = cols; p.ld = ld;
+    p.gamma = gamma; p.beta = beta; p.eps = eps; p.step = step;
+    p.out = (uint8_t *)out->data; p.out_stride = out->row_stride; p.sb = out->storage_bits;
+    p.row_bytes16 = (int)row_bytes16(out);
+    p.qmin = -(1 << (out->bits - 1)); p.qmax = (1 << (out->bits - 1)) - 1;
+    hipError_t e = layernorm_quantize_launch(p, (hipStream_t)stream);
+    return e == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }
 
 vq_status vq_prepack_weight_bytes(const vq_qmat *w, size_t *bytes) {

@@ -1,0 +1,223 @@
+// LayerNorm followed by a quantizer, without division by sigma and without square root
+// (Sec. IV-C, Eq. 5, Fig. 5).
+//
+// Phase 1 -- row statistics.  They are the incremental recurrences of Eq. 5 in fp32, elements in
+// order: that order is part of the definition (fp32 addition does not associate), so one LANE
+// walks one row and the parallelism is across the 256 rows of a workgroup (4 of its 16 waves).  The lane streams
+// its row in chunks of 16 elements, the next chunk requested before the current one is used.
+// Phase 2 -- levels.  The quantizer is the comparator of Fig. 5(b): the level is the number of
+// references (k - 1/2)*step that the normalised value exceeds, each decided as
+//     ssq((x - mu) * gamma) * n  >  ssq((k - 1/2)*step - beta) * V,      ssq(v) = v * |v|,
+// V = M_n + n*eps the (stabilised) sum of squared deviations -- sigma never appears.  Elements
+// are independent here, so the workgroup's rows are re-read wave by wave with coalesced 16-byte
+// loads by all 16 waves, four elements per lane, four rows per batch, the next batch in flight.  The comparisons are monotone in k, so
+// instead of all 2^b - 1 of them the kernel makes a guess with the hardware reciprocal square
+// root and then evaluates the comparator itself only at the guessed level and the one above,
+// stepping the guess until both agree; the guess only chooses which comparisons are made, every
+// decision is the comparator's.
+#include "layernorm.h"
+#include "vitq_dev.h"
+
+namespace vitq {
+
+namespace {
+
+constexpr int kLnRows = 64;       // rows per workgroup (one lane each in phase 1)
+constexpr int kLnThreads = 256;   // threads per workgroup: all sixteen waves work in phase 2
+constexpr int kLnWaves = kLnThreads / 64;
+
+template <bool VEC, int SB>
+__global__ __launch_bounds__(kLnThreads) void layernorm_quantize_kernel(LnParams p) {
+    __shared__ float s_mu[kLnRows], s_v[kLnRows], s_rs[kLnRows];
+    const int tid = threadIdx.x;
+    const int64_t row0 = (int64_t)blockIdx.x * kLnRows;
+    const int cols = (int)p.cols;
+    const float nf = (float)cols;
+
+    // ---- phase 1: Eq. 5, mu_i = mu_{i-1} + (x_i - mu_{i-1}) / i,
+    //                     M_i  = M_{i-1}  + (x_i - mu_{i-1}) * (x_i - mu_i)
+    if (tid < kLnRows && row0 + tid < p.rows) {
+        const float *xr = p.x + (row0 + tid) * p.ld;
+        const float *rr = p.res ? p.res + (row0 + tid) * p.ld : nullptr;
+        float mu = 0.0f, m2 = 0.0f;
+        auto step1 = [&](float xi, int i1) {      // i1 = 1-based index of the element
+            const float d1 = xi - mu;
+            mu = mu + d1 / (float)i1;
+            const float d2 = xi - mu;
+            const float pr = d1 * d2;
+            m2 = m2 + pr;
+        };
+        int j = 0;
+        if (VEC) {
+            constexpr int CH = 16;
+            const int full = cols / CH * CH;
+            auto load16 = [&](int j0, float (&v)[CH]) {
+#pragma unroll
+                for (int q = 0; q < CH / 4; ++q) {
+                    float4 a = *reinterpret_cast<const float4 *>(xr + j0 + 4 * q);
+                    if (rr) {
+                        const float4 b = *reinterpret_cast<const float4 *>(rr + j0 + 4 * q);
+                        a.x = a.x + b.x; a.y = a.y + b.y; a.z = a.z + b.z; a.w = a.w + b.w;
+                    }
+                    v[4 * q] = a.x; v[4 * q + 1] = a.y; v[4 * q + 2] = a.z; v[4 * q + 3] = a.w;
+                }
+            };
+            if (full > 0) {
+                float cur[CH], nxt[CH];
+                load16(0, cur);
+                for (; j < full; j += CH) {
+                    if (j + CH < full) load16(j + CH, nxt);
+#pragma unroll
+                    for (int i = 0; i < CH; ++i) step1(cur[i], j + i + 1);
+#pragma unroll
+                    for (int i = 0; i < CH; ++i) cur[i] = nxt[i];
+                }
+            }
+        }
+        for (; j < cols; ++j) {                   // ragged tail, unaligned rows
+            float t = xr[j];
+            if (rr) t = t + rr[j];
+            step1(t, j + 1);
+        }
+        const float ne = nf * p.eps;
+        const float V = m2 + ne;
+        s_mu[tid] = mu;
+        s_v[tid] = V;
+        s_rs[tid] = __builtin_amdgcn_rsqf(V / nf);      // for the guess only
+    }
+    __syncthreads();
+
+    // ---- phase 2: levels, one row per wave at a time, four consecutive elements per lane ----
+    const int lane = tid & 63, wave = tid >> 6;
+    const float rstep = __builtin_amdgcn_rcpf(p.step);   // for the guess only
+    const float qminf = (float)p.qmin, qmaxf = (float)p.qmax;
+    const int span = p.qmax - p.qmin;
+    const int padded = p.row_bytes16 * 8 / SB;           // columns of the 16-byte padded row
+    for (int c0 = 4 * lane; c0 < padded; c0 += 256) {
+        // this lane's four columns are the same for every row
+        float gm[4], bt[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const bool ok = c0 + i < cols;
+            gm[i] = ok ? p.gamma[c0 + i] : 0.0f;
+            bt[i] = ok ? p.beta[c0 + i] : 0.0f;
+        }
+        // Rows are taken in batches of RB; the loads of the next batch are in flight while the
+        // current one is decided (the rows no longer sit in a near cache after phase 1).
+        constexpr int RB = 4, NB = kLnRows / kLnWaves / RB;
+        auto load_batch = [&](int bi, float (&v)[RB][4]) {
+#pragma unroll
+            for (int k = 0; k < RB; ++k) {
+                const int r = wave + kLnWaves * (bi * RB + k);
+                const int64_t row = row0 + r;
+                v[k][0] = v[k][1] = v[k][2] = v[k][3] = 0.0f;
+                if (row < p.rows) {
+                    const float *xr = p.x + row * p.ld;
+                    if (VEC && c0 + 4 <= cols) {
+                        float4 a = *reinterpret_cast<const float4 *>(xr + c0);
+                        if (p.res) {
+                            const float4 b = *reinterpret_cast<const float4 *>(p.res + row * p.ld + c0);
+                            a.x = a.x + b.x; a.y = a.y + b.y; a.z = a.z + b.z; a.w = a.w + b.w;
+                        }
+                        v[k][0] = a.x; v[k][1] = a.y; v[k][2] = a.z; v[k][3] = a.w;
+                        if (p.sum_out) *reinterpret_cast<float4 *>(p.sum_out + row * p.ld + c0) = a;
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            if (c0 + i < cols) {
+                                float t = xr[c0 + i];
+                                if (p.res) t = t + p.res[row * p.ld + c0 + i];
+                                if (p.sum_out) p.sum_out[row * p.ld + c0 + i] = t;
+                                v[k][i] = t;
+                            }
+                        }
+                    }
+                }
+            }
+        };
+        float cur[RB][4], nxt[RB][4];
+        load_batch(0, cur);
+        for (int bi = 0; bi < NB; ++bi) {
+            if (row0 + wave + kLnWaves * (bi * RB) >= p.rows) break;      // no rows left for this wave
+            if (bi + 1 < NB) load_batch(bi + 1, nxt);
+            float L[RB][4], c[RB][4], V[RB];
+#pragma unroll
+            for (int k = 0; k < RB; ++k) {
+                const int r = wave + kLnWaves * (bi * RB + k);
+                const float mu = s_mu[r], rs = s_rs[r];
+                V[k] = s_v[r];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float a = cur[k][i] - mu;
+                    const float g = a * gm[i];
+                    const float gs = g * fabsf(g);
+                    L[k][i] = gs * nf;
+                    const float t = rintf(fmaf(g, rs, bt[i]) * rstep);
+                    c[k][i] = (t == t) ? __builtin_amdgcn_fmed3f(t, qminf, qmaxf) : qminf;
+                }
+            }
+            // comparator of Fig. 5(b): element (k, i) against the reference (lv - 1/2)*step
+            auto above = [&](int k, int i, float lv) {
+                const float rk = (lv - 0.5f) * p.step;
+                const float cc = rk - bt[i];
+                const float cs = cc * fabsf(cc);
+                const float R = cs * V[k];
+                return L[k][i] > R;
+            };
+            // level = qmin + #{lv : above(lv)}; above() is monotone in lv, so c is the level iff
+            // above(c) (or c == qmin) and not above(c + 1) (or c == qmax)
+            for (int it = 0; it <= span; ++it) {
+                bool moved = false;
+#pragma unroll
+                for (int k = 0; k < RB; ++k)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const bool low_ok = (c[k][i] <= qminf) || above(k, i, c[k][i]);
+                        const bool high_ok = (c[k][i] >= qmaxf) || !above(k, i, c[k][i] + 1.0f);
+                        const float d = !low_ok ? -1.0f : (!high_ok ? 1.0f : 0.0f);
+                        c[k][i] = c[k][i] + d;
+                        moved = moved || (d != 0.0f);
+                    }
+                if (__builtin_amdgcn_ballot_w64(moved) == 0) break;
+            }
+#pragma unroll
+            for (int k = 0; k < RB; ++k) {
+                const int64_t row = row0 + wave + kLnWaves * (bi * RB + k);
+                if (row < p.rows) {
+                    u32 w = 0;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const u32 field = (c0 + i < cols) ? ((u32)(int)c[k][i] & ((1u << SB) - 1u)) : 0u;
+                        w |= field << (i * SB);
+                    }
+                    uint8_t *dst = p.out + row * p.out_stride + (int64_t)c0 * SB / 8;
+                    if constexpr (SB == 8) *reinterpret_cast<u32 *>(dst) = w;
+                    else if constexpr (SB == 4) *reinterpret_cast<uint16_t *>(dst) = (uint16_t)w;
+                    else *dst = (uint8_t)w;
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < RB; ++k)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) cur[k][i] = nxt[k][i];
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t layernorm_quantize_launch(const LnParams &p, hipStream_t stream) {
+    if (p.rows == 0) return hipSuccess;
+    const bool vec = (p.cols % 4 == 0) && (p.ld % 4 == 0) && (((uintptr_t)p.x) % 16 == 0) &&
+                     (!p.res || ((uintptr_t)p.res) % 16 == 0) && (!p.sum_out || ((uintptr_t)p.sum_out) % 16 == 0);
+    const unsigned blocks = (unsigned)((p.rows + kLnRows - 1) / kLnRows);
+#define VITQ_LN_LAUNCH(V, S) hipLaunchKernelGGL((layernorm_quantize_kernel<V, S>), dim3(blocks), dim3(kLnThreads), 0, stream, p)
+    if (p.sb == 4) { if (vec) VITQ_LN_LAUNCH(true, 4); else VITQ_LN_LAUNCH(false, 4); }
+    else if (p.sb == 8) { if (vec) VITQ_LN_LAUNCH(true, 8); else VITQ_LN_LAUNCH(false, 8); }
+    else if (p.sb == 2) { if (vec) VITQ_LN_LAUNCH(true, 2); else VITQ_LN_LAUNCH(false, 2); }
+    else return hipErrorInvalidValue;
+#undef VITQ_LN_LAUNCH
+    return hipGetLastError();
+}
+
+}  // namespace vitq

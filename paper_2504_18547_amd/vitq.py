@@ -17,7 +17,7 @@ STATUS_NAMES = ["VQ_OK", "VQ_ERR_NULL", "VQ_ERR_SHAPE", "VQ_ERR_BITS", "VQ_ERR_S
 
 EXPORTS = ["vq_status_string", "vq_weight_steps", "vq_quantize", "vq_linear", "vq_matmul_qk",
            "vq_matmul_pv", "vq_attention_block_workspace", "vq_attention_block",
-           "vq_prepack_weight_bytes", "vq_prepack_weight", "vq_linear_prepacked"]
+           "vq_prepack_weight_bytes", "vq_prepack_weight", "vq_linear_prepacked", "vq_layernorm_quantize"]
 
 
 class VitqError(RuntimeError):
@@ -79,6 +79,8 @@ def lib():
         _lib.vq_prepack_weight.argtypes = [qp, vp, C.c_size_t, vp]
         _lib.vq_linear_prepacked.argtypes = [qp, C.c_float, qp, vp, vp, C.c_int32, vp, C.c_int32, vp, vp,
                                              C.c_float, qp, vp]
+        _lib.vq_layernorm_quantize.argtypes = [vp, vp, vp, C.c_int64, C.c_int64, C.c_int64, vp, vp, C.c_float,
+                                               C.c_float, qp, vp]
         for n in EXPORTS[1:]:
             getattr(_lib, n).restype = C.c_int
     return _lib
@@ -163,6 +165,14 @@ def vq_quantize(x, step, step_per_row, out):
 def vq_linear(xq, s_x, wq, s_w, s_w_per_channel, bias, act, acc_out, y_out, s_y, yq_out):
     _check(lib().vq_linear(_q(xq), float(s_x), _q(wq), _ptr(s_w), int(s_w_per_channel), _ptr(bias), int(act),
                            _ptr(acc_out), _ptr(y_out), float(s_y), _q(yq_out), _stream()), "vq_linear")
+
+
+def vq_layernorm_quantize(x, residual, sum_out, gamma, beta, eps, step, out):
+    rows, cols = x.shape
+    _check(lib().vq_layernorm_quantize(_ptr(x), _ptr(residual), _ptr(sum_out), rows, cols, x.stride(0),
+                                       _ptr(gamma), _ptr(beta), float(eps), float(step), _q(out), _stream()),
+           "vq_layernorm_quantize")
+    return out
 
 
 def vq_prepack_weight(wq):
