@@ -638,6 +638,80 @@ int vqo_layernorm_quantize(const float *x, const float *res, float *sum_out, int
     return 0;
 }
 
+/* ------------------------------------------------------------------------ */
+/* A whole pre-LayerNorm ViT block on the fp32 residual stream, composed of    */
+/* the pieces above (the paper integerizes the attention part, Sec. III, and   */
+/* gives the LayerNorm quantizer of Sec. IV-C as the module in front of it;    */
+/* the residual wiring is the standard pre-LN transformer block):              */
+/*   X_q  = LNQ1(x)                      vqo_layernorm_quantize, step s_x      */
+/*   a    = proj(attention(X_q))         block_one_image with hidden = 0       */
+/*   x1   = a + x                        fp32 add                              */
+/*   X2_q = LNQ2(x1)                     step s_x2                             */
+/*   H_q  = requant(GELU(fc1(X2_q)))     step s_h                              */
+/*   y    = fc2(H_q) + x1                fp32 add                              */
+/* x, y_out, x1_out: [B*N][D] fp32.  Dumps (nullable): xq_out, x2_out [B*N][D],*/
+/* h_out [B*N][hidden], plus the attention dumps of dmp.                       */
+/* ------------------------------------------------------------------------ */
+typedef struct vqo_ln_params {
+    const float *g1, *b1, *g2, *b2;   /* [D] each */
+    float eps;
+} vqo_ln_params;
+
+int64_t vqo_vit_block_preln(const vqo_block *blk, const vqo_ln_params *ln, const float *x,
+                            int64_t B, float *y_out, float *x1_out, int8_t *xq_out,
+                            int8_t *x2_out, int8_t *h_out, const vqo_block_dumps *dmp)
+{
+    if (blk->D % blk->H || blk->hidden <= 0) return -1;
+    const int64_t D = blk->D, N = blk->N, Hd = blk->hidden;
+    int64_t bad = 0;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 1) reduction(+ : bad)
+#endif
+    for (int64_t b = 0; b < B; ++b) {
+        vqo_block att = *blk;
+        att.hidden = 0;                               /* attention + projection, fp32 out */
+        int8_t *Xq = (int8_t *)malloc((size_t)(N * D));
+        int8_t *X2 = (int8_t *)malloc((size_t)(N * D));
+        int8_t *Hq = (int8_t *)malloc((size_t)(N * Hd));
+        float *A = (float *)malloc((size_t)(N * D) * sizeof(float));
+        float *X1 = (float *)malloc((size_t)(N * D) * sizeof(float));
+        float *T = (float *)malloc((size_t)(N * D) * sizeof(float));
+        const float *xb = x + b * N * D;
+        vqo_layernorm_quantize(xb, NULL, NULL, N, D, D, ln->g1, ln->b1, ln->eps, blk->s_x,
+                               blk->bits_a, Xq, NULL, NULL);
+        /* block_one_image indexes its outputs by image; hand it image-0 views */
+        vqo_block_dumps d0;
+        const vqo_block_dumps *dp = NULL;
+        if (dmp) {
+            const int64_t dh = D / blk->H, H = blk->H;
+            d0 = *dmp;
+            if (d0.q) d0.q += b * H * N * dh;
+            if (d0.k) d0.k += b * H * N * dh;
+            if (d0.v) d0.v += b * H * N * dh;
+            if (d0.p) d0.p += b * H * N * N;
+            if (d0.o) d0.o += b * N * D;
+            if (d0.y_attn) d0.y_attn += b * N * D;
+            d0.x2 = NULL; d0.h = NULL;
+            dp = &d0;
+        }
+        bad += block_one_image(&att, Xq, 0, A, dp);
+        /* x1 = a + x, then the second LayerNorm quantizer on x1 */
+        vqo_layernorm_quantize(A, xb, X1, N, D, D, ln->g2, ln->b2, ln->eps, blk->s_x2,
+                               blk->bits_a, X2, NULL, NULL);
+        bad += vqo_linear(X2, N, D, blk->s_x2, blk->w_fc1, Hd, blk->sw_fc1, 1, blk->b_fc1, 1,
+                          NULL, NULL, blk->s_h, blk->bits_a, Hq);
+        bad += vqo_linear(Hq, N, Hd, blk->s_h, blk->w_fc2, D, blk->sw_fc2, 1, blk->b_fc2, 0,
+                          NULL, T, 0.0f, 0, NULL);
+        for (int64_t i = 0; i < N * D; ++i) y_out[b * N * D + i] = T[i] + X1[i];
+        if (x1_out) memcpy(x1_out + b * N * D, X1, (size_t)(N * D) * sizeof(float));
+        if (xq_out) memcpy(xq_out + b * N * D, Xq, (size_t)(N * D));
+        if (x2_out) memcpy(x2_out + b * N * D, X2, (size_t)(N * D));
+        if (h_out) memcpy(h_out + b * N * Hd, Hq, (size_t)(N * Hd));
+        free(Xq); free(X2); free(Hq); free(A); free(X1); free(T);
+    }
+    return bad;
+}
+
 /* Cross-check: the direct form of Fig. 5(a) in double -- two-pass mean and    */
 /* variance, y = (x - mean) / sqrt(var + eps) * gamma + beta -- returned as y.  */
 void vqo_x_layernorm(const float *x, int64_t rows, int64_t cols, int64_t ld, const float *gamma,

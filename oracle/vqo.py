@@ -251,19 +251,9 @@ class _Dumps(C.Structure):
                 ("x2", _p), ("h", _p)]
 
 
-def attention_block(xq, B, dims, weights, steps, bits_a=4, bits_p=4, dumps=True, dump_p=False,
-                    threads=None):
-    """Run the whole chain on the CPU.
-
-    xq: int8 [B*N, D].  dims: dict(D, H, N, hidden).  weights: dict of int8 level matrices
-    w_qkv/w_proj[/w_fc1/w_fc2], fp32 step vectors sw_* and fp32 biases b_*.
-    steps: dict(s_x, s_q, s_k, s_v, s_o, s_x2, s_h, scale).
-    Returns dict with y [B*N, D] fp32 and (if dumps) the intermediates.
-    """
+def _make_block(dims, weights, steps, bits_a, bits_p):
+    """The C descriptor of a block; `keep` holds the arrays it points to."""
     D, H, N, hidden = dims["D"], dims["H"], dims["N"], dims.get("hidden", 0)
-    dh = D // H
-    xq = _c(xq, np.int8)
-    assert xq.shape == (B * N, D)
     keep = {}
 
     def w(name, shape):
@@ -290,6 +280,23 @@ def attention_block(xq, B, dims, weights, steps, bits_a=4, bits_p=4, dumps=True,
         setattr(blk, name, float(steps[name]))
     blk.s_x2 = float(steps.get("s_x2", 0.0))
     blk.s_h = float(steps.get("s_h", 0.0))
+    return blk, keep
+
+
+def attention_block(xq, B, dims, weights, steps, bits_a=4, bits_p=4, dumps=True, dump_p=False,
+                    threads=None):
+    """Run the whole chain on the CPU.
+
+    xq: int8 [B*N, D].  dims: dict(D, H, N, hidden).  weights: dict of int8 level matrices
+    w_qkv/w_proj[/w_fc1/w_fc2], fp32 step vectors sw_* and fp32 biases b_*.
+    steps: dict(s_x, s_q, s_k, s_v, s_o, s_x2, s_h, scale).
+    Returns dict with y [B*N, D] fp32 and (if dumps) the intermediates.
+    """
+    D, H, N, hidden = dims["D"], dims["H"], dims["N"], dims.get("hidden", 0)
+    dh = D // H
+    xq = _c(xq, np.int8)
+    assert xq.shape == (B * N, D)
+    blk, keep = _make_block(dims, weights, steps, bits_a, bits_p)
 
     y = np.empty((B * N, D), np.float32)
     out = dict(y=y)
@@ -367,3 +374,40 @@ def x_layernorm(x, gamma, beta, eps):
     lib().vqo_x_layernorm(_ptr(x), _i64(rows), _i64(cols), _i64(cols), _ptr(_c(gamma, np.float32)),
                           _ptr(_c(beta, np.float32)), C.c_double(eps), _ptr(y))
     return y
+
+
+class _LnParams(C.Structure):
+    _fields_ = [("g1", _p), ("b1", _p), ("g2", _p), ("b2", _p), ("eps", _f32)]
+
+
+def vit_block_preln(x, B, dims, weights, steps, ln, bits_a=4, bits_p=4, threads=None):
+    """Pre-LayerNorm block on the fp32 residual stream.  x: fp32 [B*N, D]; ln: dict(g1, b1, g2, b2, eps).
+    Returns dict(y, x1 fp32; xq, x2, h, o levels)."""
+    D, H, N, hidden = dims["D"], dims["H"], dims["N"], dims["hidden"]
+    x = _c(x, np.float32)
+    assert x.shape == (B * N, D)
+    blk, keep = _make_block(dims, weights, steps, bits_a, bits_p)
+    lp = _LnParams()
+    for k in ("g1", "b1", "g2", "b2"):
+        keep[k] = _c(ln[k], np.float32)
+        assert keep[k].size == D
+        setattr(lp, k, _ptr(keep[k]))
+    lp.eps = float(ln["eps"])
+    out = dict(y=np.empty((B * N, D), np.float32), x1=np.empty((B * N, D), np.float32),
+               xq=np.empty((B * N, D), np.int8), x2=np.empty((B * N, D), np.int8),
+               h=np.empty((B * N, hidden), np.int8), o=np.empty((B * N, D), np.int8))
+    dmp = _Dumps()
+    dmp.o = _ptr(out["o"])
+    L = lib()
+    L.vqo_vit_block_preln.restype = _i64
+    old = L.vqo_num_threads()
+    if threads is not None:
+        L.vqo_set_num_threads(_int(threads))
+    try:
+        bad = L.vqo_vit_block_preln(C.byref(blk), C.byref(lp), _ptr(x), _i64(B), _ptr(out["y"]), _ptr(out["x1"]),
+                                    _ptr(out["xq"]), _ptr(out["x2"]), _ptr(out["h"]), C.byref(dmp))
+    finally:
+        if threads is not None:
+            L.vqo_set_num_threads(_int(old))
+    assert bad == 0, "int32 overflow or bad shape in oracle chain: %d" % bad
+    return out

@@ -96,6 +96,30 @@ def block_tokens(name, images):
     return out
 
 
+def block_stream(name, images):
+    """Un-normalised fp32 residual-stream tokens [len(images), N, D] for the pre-LayerNorm block:
+    N(0,1) values with a per-token scale in [0.5, 3] and shift in [-1, 1]."""
+    d = BLOCKS[name]
+    N, D = d["N"], d["D"]
+    out = np.empty((len(images), N, D), np.float32)
+    for j, i in enumerate(images):
+        rng = np.random.default_rng([seed_for(d["cfg"]), 3000, int(i)])
+        t = rng.standard_normal((N, D))
+        out[j] = (t * rng.uniform(0.5, 3.0, (N, 1)) + rng.uniform(-1.0, 1.0, (N, 1))).astype(np.float32)
+    return out
+
+
+def block_ln_params(name):
+    """LayerNorm parameters of the pre-LayerNorm block: gamma ~ 1 + N(0, 0.1), beta ~ N(0, 0.05)."""
+    d = BLOCKS[name]
+    rng = np.random.default_rng([seed_for(d["cfg"]), 4000])
+    D = d["D"]
+    return dict(g1=(1 + 0.1 * rng.standard_normal(D)).astype(np.float32),
+                b1=(0.05 * rng.standard_normal(D)).astype(np.float32),
+                g2=(1 + 0.1 * rng.standard_normal(D)).astype(np.float32),
+                b2=(0.05 * rng.standard_normal(D)).astype(np.float32), eps=np.float32(1e-6))
+
+
 def steps_key(name, sharp, bits_w, bits_a):
     return "%s/%s/w%da%d" % (name, "sharp" if sharp else "stated", bits_w, bits_a)
 
