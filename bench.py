@@ -241,6 +241,29 @@ def main():
     out["extra"] = {"vq_layernorm_quantize": {"ms": ln_ms, "rows": B * N, "cols": D,
                                               "algorithmic_gbs": ln_bytes / (ln_ms * 1e-3) / 1e9,
                                               "note": "not part of the step; fp32 in, packed levels out"}}
+    if hidden:
+        # Also outside the step: the whole pre-LayerNorm block on the fp32 residual stream
+        # (LNQ1 -> attention -> +x -> LNQ2 -> MLP -> +x1), nominal steps for the two LayerNorm
+        # quantizers (3.5 sigma / qmax) and the GELU output.
+        qmax = float((1 << (ba - 1)) - 1)
+        st2 = dict(st)
+        st2["s_x"] = st2["s_x2"] = 3.5 / qmax
+        st2["s_h"] = 2.5 / qmax
+        blk2 = vitq.make_block_desc(dims, ba, ba, sa, wd, st2)
+        ln = {"g1": gam, "b1": bet, "g2": gam, "b2": bet, "eps": 1e-6}
+        pd = vitq.make_preln_desc(blk2, ln)
+        ws2 = torch.empty(vitq.vq_vit_block_workspace(pd, B), dtype=torch.uint8, device="cuda")
+        for i in range(4):
+            if i == 1:
+                hip.record(e0, stream)
+            vitq.vq_vit_block(pd, tokens, B, y, ws2)
+        hip.record(e1, stream)
+        torch.cuda.synchronize()
+        pl_ms = hip.elapsed_ms(e0, e1) / 3
+        out["extra"]["vq_vit_block"] = {"ms": pl_ms, "images_per_s": B / (pl_ms * 1e-3),
+                                        "tops": B * ops_img / (pl_ms * 1e-3) / 1e12,
+                                        "note": "not part of the step; fp32 stream in and out, two LayerNorm "
+                                                "quantizers and both residual adds included"}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(name, args.sharp, bw, ba, ops_img)
     print(json.dumps(out))

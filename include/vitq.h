@@ -222,6 +222,36 @@ vq_status vq_attention_block(const vq_block_desc *desc, const vq_qmat *xq, int64
                              float *y_out, void *workspace, size_t workspace_bytes,
                              void *stream);
 
+/*
+ * A whole pre-LayerNorm ViT block on the fp32 residual stream, built from the stages above
+ * (the LayerNorm quantizer of Sec. IV-C in front of the integerized attention of Sec. III-IV and,
+ * by the same principle, in front of the MLP):
+ *   X_q = LNQ1(x);  x1 = proj(attention(X_q)) + x;  X2_q = LNQ2(x1);
+ *   y   = fc2(requant(GELU(fc1(X2_q)))) + x1
+ * The two additions are fp32 adds fused into the projection / fc2 epilogues.
+ * block: as for vq_attention_block with hidden > 0; block.s_x and block.s_x2 are the steps of
+ * the two LayerNorm quantizers; block.stage_events is ignored.  ln*_gamma / ln*_beta: device
+ * fp32 [D].  dump_xq (packed [B*N][D*storage_a/8]) and dump_x1 (fp32 [B*N][D]): optional copies.
+ */
+typedef struct vq_preln_desc {
+    vq_block_desc block;
+    const float *ln1_gamma, *ln1_beta, *ln2_gamma, *ln2_beta;
+    float ln_eps;
+    int32_t reserved;
+    void *dump_xq;
+    float *dump_x1;
+} vq_preln_desc;
+
+/* Bytes of workspace vq_vit_block needs for batch B (host computation only). */
+vq_status vq_vit_block_workspace(const vq_preln_desc *desc, int64_t B, size_t *bytes);
+
+/*
+ * x: device fp32 [B*N x D], 16-byte aligned, not aliasing y_out.  y_out: device fp32 [B*N x D]
+ * (holds x1 between the stages).  workspace: device, 256-byte aligned.
+ */
+vq_status vq_vit_block(const vq_preln_desc *desc, const float *x, int64_t B, float *y_out,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

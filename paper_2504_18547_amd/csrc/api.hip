@@ -52,8 +52,9 @@ struct LinearExtra {      // head-major output of the QKV linear inside the bloc
 vq_status run_linear(const vq_qmat *xq, float s_x, const vq_qmat *wq, const float *s_w,
                      int per_channel, const float *bias, int act, int32_t *acc_out, float *y_out,
                      float s_y, const vq_qmat *yq_out, const LinearExtra *ex, hipStream_t stream,
-                     const void *wp = nullptr) {
+                     const void *wp = nullptr, const float *res = nullptr) {
     GemmParams p{};
+    p.res = res;
     p.x = (const uint8_t *)xq->data; p.x_stride = xq->row_stride; p.M = (int)xq->rows;
     p.w = (const uint8_t *)wq->data; p.w_stride = wq->row_stride; p.Nout = (int)wq->rows;
     p.K = (int)xq->cols;
@@ -390,6 +391,54 @@ vq_status weight_check(const vq_qmat *w, int64_t rows, int64_t cols, int sa, con
     return VQ_OK;
 }
 
+void block_qkv_extra(const vq_block_desc *d, const BlockLayout &L, int64_t B, uint8_t *qkv, LinearExtra &ex) {
+    ex.head_major = 1; ex.D = d->D; ex.dh = 64; ex.Ntok = d->N; ex.Bimg = (int)B; ex.Hh = d->H;
+    ex.s_q = d->s_q; ex.s_k = d->s_k; ex.s_v = d->s_v; ex.dst = qkv; ex.sb = L.sa; ex.bits = d->bits_a;
+}
+
+void block_attention_params(const vq_block_desc *d, const BlockLayout &L, const AttnParams &ap, int64_t B,
+                            uint8_t *qkv, uint8_t *obuf, AttnParams &p) {
+    const int64_t BHN = B * d->H * d->N;
+    const int64_t hrow = 64 * L.sa / 8;
+    p = ap;
+    p.q = qkv; p.k = qkv + BHN * hrow; p.v = qkv + 2 * BHN * hrow;
+    p.q_stride = p.k_stride = p.v_stride = hrow;
+    p.sb = L.sa; p.B = (int)B; p.H = d->H; p.N = d->N;
+    p.pmax = (1 << d->bits_p) - 1;
+    p.p_sb = L.sa;
+    p.spv = (1.0f / (float)p.pmax) * d->s_v;
+    p.s_o = d->s_o;
+    level_range(d->bits_a, &p.qminf, &p.qmaxf);
+    p.oq = obuf; p.oq_stride = L.act_row; p.oq_sb = L.sa;
+    p.qsplit = pick_qsplit((int64_t)B * d->H, d->N);
+    p.r_o = 1.0f / p.s_o; p.eps_o = ldexpf(1.0f, (p.qmaxf > 7.5f ? 8 : 4) - 22);
+}
+
+// Checks shared by the two block entry points (weights, steps, prepacked copies, dumps).
+vq_status block_args_check(const vq_block_desc *d, const BlockLayout &L, AttnParams *ap) {
+    vq_status st;
+    if ((st = weight_check(&d->w_qkv, 3 * (int64_t)d->D, d->D, L.sa, d->sw_qkv)) != VQ_OK) return st;
+    if ((st = weight_check(&d->w_proj, d->D, d->D, L.sa, d->sw_proj)) != VQ_OK) return st;
+    if (d->hidden) {
+        if ((st = weight_check(&d->w_fc1, d->hidden, d->D, L.sa, d->sw_fc1)) != VQ_OK) return st;
+        if ((st = weight_check(&d->w_fc2, d->D, d->hidden, L.sa, d->sw_fc2)) != VQ_OK) return st;
+        if (!good_step(d->s_x2) || !good_step(d->s_h)) return VQ_ERR_STEP;
+    }
+    if (!good_step(d->s_x) || !good_step(d->s_q) || !good_step(d->s_k) || !good_step(d->s_v) ||
+        !good_step(d->s_o) || !good_step(d->scale))
+        return VQ_ERR_STEP;
+    if (!scaled_alpha(d->s_q, d->s_k, d->scale, L.sa == 4 ? 8 : 0, ap)) return VQ_ERR_STEP;
+    for (void *dp : {d->dump_qkv, d->dump_o, d->dump_x2, d->dump_h})
+        if (((uintptr_t)dp) % 16 != 0) return VQ_ERR_STRIDE;
+    const int have = (d->wp_qkv != nullptr) + (d->wp_proj != nullptr) + (d->wp_fc1 != nullptr) +
+                     (d->wp_fc2 != nullptr);
+    if (have != 0 && have != (d->hidden ? 4 : 2)) return VQ_ERR_NULL;
+    if (have != 0 && (!d->wp_qkv || !d->wp_proj)) return VQ_ERR_NULL;
+    for (const void *wp : {d->wp_qkv, d->wp_proj, d->wp_fc1, d->wp_fc2})
+        if (((uintptr_t)wp) % 16 != 0) return VQ_ERR_STRIDE;
+    return VQ_OK;
+}
+
 }  // namespace
 
 vq_status vq_attention_block_workspace(const vq_block_desc *desc, int64_t B, size_t *bytes) {
@@ -409,41 +458,19 @@ vq_status vq_attention_block(const vq_block_desc *d, const vq_qmat *xq, int64_t 
     hipStream_t stream = (hipStream_t)stream_;
     if ((st = check_qmat(xq, 0)) != VQ_OK) return st;
     if (xq->rows != L.M || xq->cols != d->D || xq->storage_bits != L.sa) return VQ_ERR_SHAPE;
-    if ((st = weight_check(&d->w_qkv, 3 * (int64_t)d->D, d->D, L.sa, d->sw_qkv)) != VQ_OK) return st;
-    if ((st = weight_check(&d->w_proj, d->D, d->D, L.sa, d->sw_proj)) != VQ_OK) return st;
-    if (d->hidden) {
-        if ((st = weight_check(&d->w_fc1, d->hidden, d->D, L.sa, d->sw_fc1)) != VQ_OK) return st;
-        if ((st = weight_check(&d->w_fc2, d->D, d->hidden, L.sa, d->sw_fc2)) != VQ_OK) return st;
-        if (!good_step(d->s_x2) || !good_step(d->s_h)) return VQ_ERR_STEP;
-    }
-    if (!good_step(d->s_x) || !good_step(d->s_q) || !good_step(d->s_k) || !good_step(d->s_v) ||
-        !good_step(d->s_o) || !good_step(d->scale))
-        return VQ_ERR_STEP;
     AttnParams ap{};
-    if (!scaled_alpha(d->s_q, d->s_k, d->scale, L.sa == 4 ? 8 : 0, &ap)) return VQ_ERR_STEP;
+    if ((st = block_args_check(d, L, &ap)) != VQ_OK) return st;
     if (B == 0) return VQ_OK;
     if (!y_out) return VQ_ERR_NULL;
     if (!workspace || workspace_bytes < L.total) return VQ_ERR_WORKSPACE;
     if (((uintptr_t)workspace) % 256 != 0) return VQ_ERR_WORKSPACE;
     if (((uintptr_t)y_out) % 16 != 0) return VQ_ERR_STRIDE;
-    for (void *dp : {d->dump_qkv, d->dump_o, d->dump_x2, d->dump_h})
-        if (((uintptr_t)dp) % 16 != 0) return VQ_ERR_STRIDE;
-    {
-        const int have = (d->wp_qkv != nullptr) + (d->wp_proj != nullptr) + (d->wp_fc1 != nullptr) +
-                         (d->wp_fc2 != nullptr);
-        if (have != 0 && have != (d->hidden ? 4 : 2)) return VQ_ERR_NULL;
-        if (have != 0 && (!d->wp_qkv || !d->wp_proj)) return VQ_ERR_NULL;
-        for (const void *wp : {d->wp_qkv, d->wp_proj, d->wp_fc1, d->wp_fc2})
-            if (((uintptr_t)wp) % 16 != 0) return VQ_ERR_STRIDE;
-    }
 
     uint8_t *ws = (uint8_t *)workspace;
     uint8_t *qkv = d->dump_qkv ? (uint8_t *)d->dump_qkv : ws + L.qkv_off;
     uint8_t *obuf = d->dump_o ? (uint8_t *)d->dump_o : ws + L.o_off;
     uint8_t *x2buf = d->dump_x2 ? (uint8_t *)d->dump_x2 : ws + L.x2_off;
     uint8_t *hbuf = d->dump_h ? (uint8_t *)d->dump_h : ws + L.h_off;
-    const int64_t BHN = B * d->H * d->N;
-    const int64_t hrow = 64 * L.sa / 8;
 
     int ev = 0;
     auto mark = [&]() {
@@ -453,8 +480,7 @@ vq_status vq_attention_block(const vq_block_desc *d, const vq_qmat *xq, int64_t 
     mark();
     // 1. QKV linear; the epilogue requantizes Q, K, V with their own steps, head-major
     LinearExtra ex;
-    ex.head_major = 1; ex.D = d->D; ex.dh = 64; ex.Ntok = d->N; ex.Bimg = (int)B; ex.Hh = d->H;
-    ex.s_q = d->s_q; ex.s_k = d->s_k; ex.s_v = d->s_v; ex.dst = qkv; ex.sb = L.sa; ex.bits = d->bits_a;
+    block_qkv_extra(d, L, B, qkv, ex);
     st = run_linear(xq, d->s_x, &d->w_qkv, d->sw_qkv, 1, d->b_qkv, 0, nullptr, nullptr, 0.0f, nullptr, &ex,
                     stream, d->wp_qkv);
     if (st != VQ_OK) return st;
@@ -465,18 +491,8 @@ vq_status vq_attention_block(const vq_block_desc *d, const vq_qmat *xq, int64_t 
     oq.data = obuf; oq.bits = d->bits_a; oq.storage_bits = L.sa; oq.rows = L.M; oq.cols = d->D;
     oq.row_stride = L.act_row;
     {
-        AttnParams p = ap;
-        p.q = qkv; p.k = qkv + BHN * hrow; p.v = qkv + 2 * BHN * hrow;
-        p.q_stride = p.k_stride = p.v_stride = hrow;
-        p.sb = L.sa; p.B = (int)B; p.H = d->H; p.N = d->N;
-        p.pmax = (1 << d->bits_p) - 1;
-        p.p_sb = L.sa;
-        p.spv = (1.0f / (float)p.pmax) * d->s_v;
-        p.s_o = d->s_o;
-        level_range(d->bits_a, &p.qminf, &p.qmaxf);
-        p.oq = obuf; p.oq_stride = L.act_row; p.oq_sb = L.sa;
-        p.qsplit = pick_qsplit((int64_t)B * d->H, d->N);
-        p.r_o = 1.0f / p.s_o; p.eps_o = ldexpf(1.0f, (p.qmaxf > 7.5f ? 8 : 4) - 22);
+        AttnParams p;
+        block_attention_params(d, L, ap, B, qkv, obuf, p);
         if (attention_launch(p, kAttnFused, stream) != hipSuccess) return VQ_ERR_HIP;
     }
     mark();
@@ -507,6 +523,94 @@ vq_status vq_attention_block(const vq_block_desc *d, const vq_qmat *xq, int64_t 
                     stream, d->wp_fc2);
     mark();
     return st;
+}
+
+vq_status vq_vit_block_workspace(const vq_preln_desc *desc, int64_t B, size_t *bytes) {
+    if (!bytes) return VQ_ERR_NULL;
+    if (!desc) return VQ_ERR_NULL;
+    BlockLayout L;
+    vq_status st = block_check(&desc->block, B, &L);
+    if (st != VQ_OK) return st;
+    if (desc->block.hidden <= 0) return VQ_ERR_SHAPE;
+    *bytes = L.total + align256((size_t)(L.M * L.act_row));      // + the LayerNorm-1 output X_q
+    return VQ_OK;
+}
+
+vq_status vq_vit_block(const vq_preln_desc *desc, const float *x, int64_t B, float *y_out, void *workspace,
+                       size_t workspace_bytes, void *stream_) {
+    if (!desc) return VQ_ERR_NULL;
+    const vq_block_desc *d = &desc->block;
+    BlockLayout L;
+    vq_status st = block_check(d, B, &L);
+    if (st != VQ_OK) return st;
+    if (d->hidden <= 0) return VQ_ERR_SHAPE;
+    hipStream_t stream = (hipStream_t)stream_;
+    AttnParams ap{};
+    if ((st = block_args_check(d, L, &ap)) != VQ_OK) return st;
+    if (!(desc->ln_eps >= 0.0f) || !isfinite(desc->ln_eps)) return VQ_ERR_STEP;
+    if (!desc->ln1_gamma || !desc->ln1_beta || !desc->ln2_gamma || !desc->ln2_beta) return VQ_ERR_NULL;
+    if (B == 0) return VQ_OK;
+    if (!x || !y_out) return VQ_ERR_NULL;
+    if (x == y_out) return VQ_ERR_NULL;                   // the input stream is read again after y is written
+    const size_t xq_bytes = align256((size_t)(L.M * L.act_row));
+    if (!workspace || workspace_bytes < L.total + xq_bytes) return VQ_ERR_WORKSPACE;
+    if (((uintptr_t)workspace) % 256 != 0) return VQ_ERR_WORKSPACE;
+    if (((uintptr_t)y_out) % 16 != 0 || ((uintptr_t)x) % 16 != 0 || ((uintptr_t)desc->dump_xq) % 16 != 0)
+        return VQ_ERR_STRIDE;
+
+    uint8_t *ws = (uint8_t *)workspace;
+    uint8_t *qkv = d->dump_qkv ? (uint8_t *)d->dump_qkv : ws + L.qkv_off;
+    uint8_t *obuf = d->dump_o ? (uint8_t *)d->dump_o : ws + L.o_off;
+    uint8_t *x2buf = d->dump_x2 ? (uint8_t *)d->dump_x2 : ws + L.x2_off;
+    uint8_t *hbuf = d->dump_h ? (uint8_t *)d->dump_h : ws + L.h_off;
+    uint8_t *xqbuf = desc->dump_xq ? (uint8_t *)desc->dump_xq : ws + L.total;
+    auto act = [&](uint8_t *data, int64_t cols, int64_t stride) {
+        vq_qmat m{};
+        m.data = data; m.bits = d->bits_a; m.storage_bits = L.sa; m.rows = L.M; m.cols = cols; m.row_stride = stride;
+        return m;
+    };
+    const vq_qmat xq = act(xqbuf, d->D, L.act_row), oq = act(obuf, d->D, L.act_row);
+    const vq_qmat x2 = act(x2buf, d->D, L.act_row), hq = act(hbuf, d->hidden, L.h_row);
+    int qmin = -(1 << (d->bits_a - 1)), qmax = (1 << (d->bits_a - 1)) - 1;
+    auto lnq = [&](const float *src, const float *gamma, const float *beta, float step, const vq_qmat &out) {
+        LnParams p{};
+        p.x = src; p.rows = L.M; p.cols = d->D; p.ld = d->D; p.gamma = gamma; p.beta = beta;
+        p.eps = desc->ln_eps; p.step = step;
+        p.out = (uint8_t *)out.data; p.out_stride = out.row_stride; p.sb = out.storage_bits;
+        p.row_bytes16 = (int)row_bytes16(&out); p.qmin = qmin; p.qmax = qmax;
+        return layernorm_quantize_launch(p, stream) == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+    };
+
+    // 1. X_q = LayerNorm-1 quantizer of the stream
+    if ((st = lnq(x, desc->ln1_gamma, desc->ln1_beta, d->s_x, xq)) != VQ_OK) return st;
+    // 2. QKV linear, fused attention
+    LinearExtra ex;
+    block_qkv_extra(d, L, B, qkv, ex);
+    st = run_linear(&xq, d->s_x, &d->w_qkv, d->sw_qkv, 1, d->b_qkv, 0, nullptr, nullptr, 0.0f, nullptr, &ex,
+                    stream, d->wp_qkv);
+    if (st != VQ_OK) return st;
+    {
+        AttnParams p;
+        block_attention_params(d, L, ap, B, qkv, obuf, p);
+        if (attention_launch(p, kAttnFused, stream) != hipSuccess) return VQ_ERR_HIP;
+    }
+    // 3. x1 = proj(O_q) + x, written to y_out
+    st = run_linear(&oq, d->s_o, &d->w_proj, d->sw_proj, 1, d->b_proj, 0, nullptr, y_out, 0.0f, nullptr, nullptr,
+                    stream, d->wp_proj, x);
+    if (st != VQ_OK) return st;
+    if (desc->dump_x1) {
+        if (hipMemcpyAsync(desc->dump_x1, y_out, (size_t)L.M * d->D * sizeof(float), hipMemcpyDeviceToDevice,
+                           stream) != hipSuccess)
+            return VQ_ERR_HIP;
+    }
+    // 4. X2_q = LayerNorm-2 quantizer of x1
+    if ((st = lnq(y_out, desc->ln2_gamma, desc->ln2_beta, d->s_x2, x2)) != VQ_OK) return st;
+    // 5. fc1 + GELU + requant, 6. y = fc2(H_q) + x1, in place
+    st = run_linear(&x2, d->s_x2, &d->w_fc1, d->sw_fc1, 1, d->b_fc1, 1, nullptr, nullptr, d->s_h, &hq, nullptr,
+                    stream, d->wp_fc1);
+    if (st != VQ_OK) return st;
+    return run_linear(&hq, d->s_h, &d->w_fc2, d->sw_fc2, 1, d->b_fc2, 0, nullptr, y_out, 0.0f, nullptr, nullptr,
+                      stream, d->wp_fc2, y_out);
 }
 
 }  // extern "C"

@@ -15,6 +15,7 @@ struct GemmParams {
     float s_x; const float *s_w; int s_w_per_channel; const float *bias; int act;
     // outputs (each nullable)
     int32_t *acc_out; float *y_out; int vec_ok;      // vec_ok: Nout % 4 == 0 (aligned rows)
+    const float *res;                                // nullable [M x Nout]: added to y (may alias y_out)
     uint8_t *yq; int64_t yq_stride; int yq_sb; int yq_row_bytes16;
     float s_y[3]; float qminf, qmaxf;
     // constants of the guarded fast requantization (see gemm.hip): 1/s_y, the guard widths

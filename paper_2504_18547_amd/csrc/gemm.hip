@@ -110,6 +110,7 @@ __device__ __forceinline__ void epilogue_generic(const GemmParams &p, const v16i
         a[r] = acc[r] >> shift;
         float v = fmaf((float)a[r], sc, bsr);
         if (p.act == 1) v = gelu_tanh(v);
+        if (p.res && ok && m < p.M) v = v + p.res[(int64_t)m * p.Nout + c];
         y[r] = v;
     }
     const bool vec = full && p.vec_ok;
@@ -168,12 +169,15 @@ __device__ __forceinline__ void epilogue_f32(const GemmParams &p, const v16i &ac
     float sc = scs;
     if (!fold_ok) sc = p.s_x * p.s_w[p.s_w_per_channel ? ch : 0];   // subnormal-small scales: unfolded
     float *out = p.y_out + (int64_t)m0 * p.Nout + ch;
+    const float *res = p.res ? p.res + (int64_t)m0 * p.Nout + ch : nullptr;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int dm = 8 * (r >> 2) + (r & 3);
         if (m0 + dm < p.M) {
             const int a = fold_ok ? acc[r] : (acc[r] >> shift);
-            out[(int64_t)dm * p.Nout] = fmaf((float)a, sc, bs);
+            float y = fmaf((float)a, sc, bs);
+            if (res) y = y + res[(int64_t)dm * p.Nout];     // residual stream (each element is read
+            out[(int64_t)dm * p.Nout] = y;                  // by the lane that then writes it)
         }
     }
 }

@@ -17,7 +17,8 @@ STATUS_NAMES = ["VQ_OK", "VQ_ERR_NULL", "VQ_ERR_SHAPE", "VQ_ERR_BITS", "VQ_ERR_S
 
 EXPORTS = ["vq_status_string", "vq_weight_steps", "vq_quantize", "vq_linear", "vq_matmul_qk",
            "vq_matmul_pv", "vq_attention_block_workspace", "vq_attention_block",
-           "vq_prepack_weight_bytes", "vq_prepack_weight", "vq_linear_prepacked", "vq_layernorm_quantize"]
+           "vq_prepack_weight_bytes", "vq_prepack_weight", "vq_linear_prepacked", "vq_layernorm_quantize",
+           "vq_vit_block_workspace", "vq_vit_block"]
 
 
 class VitqError(RuntimeError):
@@ -48,6 +49,12 @@ class vq_block_desc(C.Structure):
                 ("dump_h", C.c_void_p), ("stage_events", C.POINTER(C.c_void_p)),
                 ("wp_qkv", C.c_void_p), ("wp_proj", C.c_void_p), ("wp_fc1", C.c_void_p),
                 ("wp_fc2", C.c_void_p)]
+
+
+class vq_preln_desc(C.Structure):
+    _fields_ = [("block", vq_block_desc), ("ln1_gamma", C.c_void_p), ("ln1_beta", C.c_void_p),
+                ("ln2_gamma", C.c_void_p), ("ln2_beta", C.c_void_p), ("ln_eps", C.c_float),
+                ("reserved", C.c_int32), ("dump_xq", C.c_void_p), ("dump_x1", C.c_void_p)]
 
 
 _lib = None
@@ -81,6 +88,8 @@ def lib():
                                              C.c_float, qp, vp]
         _lib.vq_layernorm_quantize.argtypes = [vp, vp, vp, C.c_int64, C.c_int64, C.c_int64, vp, vp, C.c_float,
                                                C.c_float, qp, vp]
+        _lib.vq_vit_block_workspace.argtypes = [C.POINTER(vq_preln_desc), C.c_int64, C.POINTER(C.c_size_t)]
+        _lib.vq_vit_block.argtypes = [C.POINTER(vq_preln_desc), vp, C.c_int64, vp, vp, C.c_size_t, vp]
         for n in EXPORTS[1:]:
             getattr(_lib, n).restype = C.c_int
     return _lib
@@ -234,3 +243,27 @@ def vq_attention_block(desc, xq, B, y_out, workspace):
     _check(lib().vq_attention_block(C.byref(desc), _q(xq), int(B), _ptr(y_out), _ptr(workspace),
                                     workspace.numel() * workspace.element_size() if workspace is not None else 0,
                                     _stream()), "vq_attention_block")
+
+
+def make_preln_desc(block_desc, ln, dump_xq=None, dump_x1=None):
+    """block_desc: a vq_block_desc (hidden > 0); ln: dict of device tensors g1, b1, g2, b2 and eps."""
+    d = vq_preln_desc()
+    d.block = block_desc
+    d.ln1_gamma, d.ln1_beta = ln["g1"].data_ptr(), ln["b1"].data_ptr()
+    d.ln2_gamma, d.ln2_beta = ln["g2"].data_ptr(), ln["b2"].data_ptr()
+    d.ln_eps = float(ln["eps"])
+    d.dump_xq = dump_xq.data_ptr() if dump_xq is not None else None
+    d.dump_x1 = dump_x1.data_ptr() if dump_x1 is not None else None
+    return d
+
+
+def vq_vit_block_workspace(desc, B):
+    n = C.c_size_t()
+    _check(lib().vq_vit_block_workspace(C.byref(desc), int(B), C.byref(n)), "vq_vit_block_workspace")
+    return n.value
+
+
+def vq_vit_block(desc, x, B, y_out, workspace):
+    _check(lib().vq_vit_block(C.byref(desc), _ptr(x), int(B), _ptr(y_out), _ptr(workspace),
+                              workspace.numel() * workspace.element_size() if workspace is not None else 0,
+                              _stream()), "vq_vit_block")
