@@ -417,6 +417,11 @@ int64_t vqo_matmul_pv(const uint8_t *p, const int8_t *v, int64_t B, int64_t H, i
 /* part of this chain.  Images are independent; the loop over images is the    */
 /* only parallel loop (OpenMP, when compiled with it).                         */
 /* ------------------------------------------------------------------------ */
+int vqo_layernorm_quantize(const float *x, const float *res, float *sum_out, int64_t rows,
+                           int64_t cols, int64_t ld, const float *gamma, const float *beta,
+                           float eps, float step, int bits, int8_t *q, float *mu_out,
+                           float *m2_out);
+
 typedef struct vqo_block {
     int64_t D, H, N, hidden;   /* hidden = 0: attention only                  */
     int32_t bits_a, bits_p;    /* activation bits (signed), P bits (unsigned) */
@@ -436,8 +441,27 @@ typedef struct vqo_block_dumps {  /* all nullable; sizes for B images          *
     int8_t *h;             /* [B*N][hidden]                                   */
 } vqo_block_dumps;
 
+/* Per-head LayerNorm of Q and K (Sec. III, Fig. 1(b); Table I lists a LayerNorm */
+/* of 2 x O elements after the Q and the K linear, none after V): gamma, beta    */
+/* are [2D] (the Q channels, then the K channels), each head's 64 channels are   */
+/* normalised on their own by vqo_layernorm_quantize; s_q, s_k are then the      */
+/* steps of those quantizers.  NULL: the plain requantization of the block.      */
+typedef struct vqo_qkln {
+    const float *gamma, *beta;
+    float eps;
+} vqo_qkln;
+
+static int64_t block_one_image_ln(const vqo_block *blk, const vqo_qkln *qkln, const int8_t *xq,
+                                  int64_t b, float *y_out, const vqo_block_dumps *dmp);
+
 static int64_t block_one_image(const vqo_block *blk, const int8_t *xq, int64_t b,
                                float *y_out, const vqo_block_dumps *dmp)
+{
+    return block_one_image_ln(blk, NULL, xq, b, y_out, dmp);
+}
+
+static int64_t block_one_image_ln(const vqo_block *blk, const vqo_qkln *qkln, const int8_t *xq,
+                                  int64_t b, float *y_out, const vqo_block_dumps *dmp)
 {
     const int64_t D = blk->D, H = blk->H, N = blk->N, dh = D / H, Hd = blk->hidden;
     int64_t bad = 0;
@@ -455,9 +479,19 @@ static int64_t block_one_image(const vqo_block *blk, const int8_t *xq, int64_t b
         for (int64_t c = 0; c < 3 * D; ++c) {
             int64_t which = c / D, h = (c % D) / dh, d = c % dh;
             float step = which == 0 ? blk->s_q : (which == 1 ? blk->s_k : blk->s_v);
+            if (qkln && which < 2) continue;          /* Q and K: LayerNorm quantizer, below */
             hm[((which * H + h) * N + n) * dh + d] =
                 (int8_t)quantize_one(Y[n * 3 * D + c], step, qmin, qmax);
         }
+    if (qkln) {
+        /* one head of one token at a time: dh consecutive channels of the row, own statistics */
+        for (int64_t which = 0; which < 2; ++which)
+            for (int64_t h = 0; h < H; ++h)
+                vqo_layernorm_quantize(Y + which * D + h * dh, NULL, NULL, N, dh, 3 * D,
+                                       qkln->gamma + which * D + h * dh, qkln->beta + which * D + h * dh,
+                                       qkln->eps, which == 0 ? blk->s_q : blk->s_k, blk->bits_a,
+                                       hm + (which * H + h) * N * dh, NULL, NULL);
+    }
     const int8_t *Q = hm, *K = hm + H * N * dh, *V = hm + 2 * H * N * dh;
 
     bad += vqo_matmul_qk(Q, K, 1, H, N, dh, blk->s_q, blk->s_k, blk->scale, blk->bits_p, NULL, P);
@@ -512,6 +546,20 @@ int64_t vqo_attention_block(const vqo_block *blk, const int8_t *xq, int64_t B,
 #endif
     for (int64_t b = 0; b < B; ++b)
         bad += block_one_image(blk, xq + b * blk->N * blk->D, b, y_out, dmp);
+    return bad;
+}
+
+/* The same chain with the per-head LayerNorm quantizers on Q and K.             */
+int64_t vqo_attention_block_qkln(const vqo_block *blk, const vqo_qkln *qkln, const int8_t *xq,
+                                 int64_t B, float *y_out, const vqo_block_dumps *dmp)
+{
+    if (blk->D % blk->H) return -1;
+    int64_t bad = 0;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 1) reduction(+ : bad)
+#endif
+    for (int64_t b = 0; b < B; ++b)
+        bad += block_one_image_ln(blk, qkln, xq + b * blk->N * blk->D, b, y_out, dmp);
     return bad;
 }
 

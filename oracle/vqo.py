@@ -283,13 +283,19 @@ def _make_block(dims, weights, steps, bits_a, bits_p):
     return blk, keep
 
 
+class _QkLn(C.Structure):
+    _fields_ = [("gamma", _p), ("beta", _p), ("eps", _f32)]
+
+
 def attention_block(xq, B, dims, weights, steps, bits_a=4, bits_p=4, dumps=True, dump_p=False,
-                    threads=None):
+                    threads=None, qkln=None):
     """Run the whole chain on the CPU.
 
     xq: int8 [B*N, D].  dims: dict(D, H, N, hidden).  weights: dict of int8 level matrices
     w_qkv/w_proj[/w_fc1/w_fc2], fp32 step vectors sw_* and fp32 biases b_*.
     steps: dict(s_x, s_q, s_k, s_v, s_o, s_x2, s_h, scale).
+    qkln: None, or dict(gamma [2D], beta [2D], eps): Q and K go through a per-head LayerNorm
+    quantizer (steps s_q, s_k) instead of the plain requantization.
     Returns dict with y [B*N, D] fp32 and (if dumps) the intermediates.
     """
     D, H, N, hidden = dims["D"], dims["H"], dims["N"], dims.get("hidden", 0)
@@ -322,8 +328,17 @@ def attention_block(xq, B, dims, weights, steps, bits_a=4, bits_p=4, dumps=True,
     if threads is not None:
         L.vqo_set_num_threads(_int(threads))
     try:
-        bad = L.vqo_attention_block(C.byref(blk), _ptr(xq), _i64(B), _ptr(y),
-                                    C.byref(dmp) if dmp is not None else None)
+        if qkln is None:
+            bad = L.vqo_attention_block(C.byref(blk), _ptr(xq), _i64(B), _ptr(y),
+                                        C.byref(dmp) if dmp is not None else None)
+        else:
+            ql = _QkLn()
+            keep["qk_gamma"], keep["qk_beta"] = _c(qkln["gamma"], np.float32), _c(qkln["beta"], np.float32)
+            assert keep["qk_gamma"].size == 2 * D and keep["qk_beta"].size == 2 * D
+            ql.gamma, ql.beta, ql.eps = _ptr(keep["qk_gamma"]), _ptr(keep["qk_beta"]), float(qkln["eps"])
+            L.vqo_attention_block_qkln.restype = _i64
+            bad = L.vqo_attention_block_qkln(C.byref(blk), C.byref(ql), _ptr(xq), _i64(B), _ptr(y),
+                                             C.byref(dmp) if dmp is not None else None)
     finally:
         if threads is not None:
             L.vqo_set_num_threads(_int(old))
