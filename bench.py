@@ -241,6 +241,26 @@ def main():
     out["extra"] = {"vq_layernorm_quantize": {"ms": ln_ms, "rows": B * N, "cols": D,
                                               "algorithmic_gbs": ln_bytes / (ln_ms * 1e-3) / 1e9,
                                               "note": "not part of the step; fp32 in, packed levels out"}}
+    # Outside the step: the same chain with per-head LayerNorm quantizers on Q and K (the paper's
+    # own attention topology, Table I); nominal steps 3 sigma / qmax for Q and K.
+    qmax_a = float((1 << (ba - 1)) - 1)
+    st3 = dict(st)
+    st3["s_q"] = st3["s_k"] = 3.0 / qmax_a
+    qk_g = torch.ones(2 * D, device="cuda")
+    qk_b = torch.zeros(2 * D, device="cuda")
+    desc3 = vitq.make_block_desc(dims, ba, ba, sa, wd, st3, qkln={"gamma": qk_g, "beta": qk_b, "eps": 1e-6})
+    ws3 = torch.empty(vitq.vq_attention_block_workspace(desc3, B), dtype=torch.uint8, device="cuda")
+    for i in range(4):
+        if i == 1:
+            hip.record(e0, stream)
+        vitq.vq_attention_block(desc3, xq, B, y, ws3)
+    hip.record(e1, stream)
+    torch.cuda.synchronize()
+    qk_ms = hip.elapsed_ms(e0, e1) / 3
+    out["extra"]["vq_attention_block_qk_layernorm"] = {
+        "ms": qk_ms, "images_per_s": B / (qk_ms * 1e-3),
+        "note": "not part of the step; QKV linear in fp32, then vq_qkv_headnorm, then the same stages"}
+    del ws3
     if hidden:
         # Also outside the step: the whole pre-LayerNorm block on the fp32 residual stream
         # (LNQ1 -> attention -> +x -> LNQ2 -> MLP -> +x1), nominal steps for the two LayerNorm

@@ -167,6 +167,14 @@ typedef struct vq_block_desc {
      * nullable, all four or none; hidden == 0: the first two).  With 4-bit activation storage
      * the linears then read these instead of unpacking the packed weights in every tile.     */
     const void *wp_qkv, *wp_proj, *wp_fc1, *wp_fc2;
+    /* Optional per-head LayerNorm of Q and K (Fig. 1(b), Table I: a LayerNorm of 2 x O elements
+     * after the Q and the K linear, none after V).  qk_gamma, qk_beta: device fp32 [2D] (Q
+     * channels, then K channels), nullable together.  When given, the QKV linear writes fp32
+     * into the workspace and vq_qkv_headnorm turns it into the packed Q, K, V: s_q and s_k are
+     * then the steps of the two LayerNorm quantizers, and the scalar s_x is cancelled by them.  */
+    const float *qk_gamma, *qk_beta;
+    float qk_eps;
+    int32_t reserved2;
 } vq_block_desc;
 
 /*
@@ -210,6 +218,17 @@ vq_status vq_linear_prepacked(const vq_qmat *xq, float s_x, const vq_qmat *wq, c
 vq_status vq_layernorm_quantize(const float *x, const float *residual, float *sum_out, int64_t rows,
                                 int64_t cols, int64_t ld, const float *gamma, const float *beta,
                                 float eps, float step, const vq_qmat *out, void *stream);
+
+/*
+ * Q, K, V of a QKV linear, y fp32 [B*N x 3D] (leading dimension ld, elements; D = 64*H), to the
+ * packed head-major operands of the attention, out = [3][B][H][N][64*storage_bits/8] bytes:
+ * every 64-channel head of Q and of K goes through the LayerNorm quantizer of
+ * vq_layernorm_quantize on its own (statistics per token and head, gamma / beta [2D], steps
+ * s_q / s_k), V through the plain quantizer with step s_v.
+ */
+vq_status vq_qkv_headnorm(const float *y, int64_t ld, int32_t B, int32_t H, int32_t N,
+                          const float *gamma, const float *beta, float eps, float s_q, float s_k,
+                          float s_v, int32_t bits, int32_t storage_bits, void *out, void *stream);
 
 /* Bytes of workspace vq_attention_block needs for batch B (host computation only). */
 vq_status vq_attention_block_workspace(const vq_block_desc *desc, int64_t B, size_t *bytes);

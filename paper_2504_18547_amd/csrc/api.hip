@@ -223,6 +223,26 @@ vq_status vq_layernorm_quantize(const float *x, const float *residual, float *su
     return e == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }
 
+vq_status vq_qkv_headnorm(const float *y, int64_t ld, int32_t B, int32_t H, int32_t N, const float *gamma,
+                          const float *beta, float eps, float s_q, float s_k, float s_v, int32_t bits,
+                          int32_t storage_bits, void *out, void *stream) {
+    if (B < 0 || H <= 0 || N <= 0 || ld < 3 * 64 * (int64_t)H || ld % 4 != 0) return VQ_ERR_SHAPE;
+    if ((int64_t)B * N * 3 * H > INT32_MAX) return VQ_ERR_SHAPE;
+    if (storage_bits != 4 && storage_bits != 8) return VQ_ERR_BITS;
+    if (bits < 2 || bits > storage_bits) return VQ_ERR_BITS;
+    if (!good_step(s_q) || !good_step(s_k) || !good_step(s_v) || !(eps >= 0.0f) || !isfinite(eps))
+        return VQ_ERR_STEP;
+    if (B == 0) return VQ_OK;
+    if (!y || !gamma || !beta || !out) return VQ_ERR_NULL;
+    if (((uintptr_t)y) % 16 || ((uintptr_t)out) % 16 || ((uintptr_t)gamma) % 16 || ((uintptr_t)beta) % 16)
+        return VQ_ERR_STRIDE;
+    HeadNormParams hp{};
+    hp.y = y; hp.ld = ld; hp.B = B; hp.H = H; hp.N = N; hp.D = 64 * H;
+    hp.gamma = gamma; hp.beta = beta; hp.eps = eps; hp.s_q = s_q; hp.s_k = s_k; hp.s_v = s_v;
+    hp.out = (uint8_t *)out; hp.sb = storage_bits; hp.qmin = -(1 << (bits - 1)); hp.qmax = (1 << (bits - 1)) - 1;
+    return qkv_headnorm_launch(hp, (hipStream_t)stream) == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
 vq_status vq_prepack_weight_bytes(const vq_qmat *w, size_t *bytes) {
     if (!bytes) return VQ_ERR_NULL;
     vq_status st = check_qmat(w, 0);
@@ -352,7 +372,7 @@ namespace {
 
 struct BlockLayout {
     int64_t M; int sa; int dh;
-    size_t qkv_off, o_off, x2_off, h_off, total;
+    size_t qkv_off, o_off, x2_off, h_off, y3_off, total;
     int64_t qkv_bytes, act_row, h_row;
 };
 
@@ -378,6 +398,7 @@ vq_status block_check(const vq_block_desc *d, int64_t B, BlockLayout *L) {
     L->o_off = off;   off += align256((size_t)(L->M * L->act_row));
     L->x2_off = off;  off += d->hidden ? align256((size_t)(L->M * L->act_row)) : 0;
     L->h_off = off;   off += d->hidden ? align256((size_t)(L->M * L->h_row)) : 0;
+    L->y3_off = off;  off += d->qk_gamma ? align256((size_t)L->M * 3 * d->D * sizeof(float)) : 0;   // fp32 QKV
     L->total = off;
     return VQ_OK;
 }
@@ -414,6 +435,28 @@ void block_attention_params(const vq_block_desc *d, const BlockLayout &L, const 
     p.r_o = 1.0f / p.s_o; p.eps_o = ldexpf(1.0f, (p.qmaxf > 7.5f ? 8 : 4) - 22);
 }
 
+// QKV stage of both block entry points: the linear with the head-major requantizing epilogue, or,
+// with the per-head LayerNorm of Q and K, the linear in fp32 followed by vq_qkv_headnorm's kernel.
+vq_status run_qkv_stage(const vq_block_desc *d, const BlockLayout &L, const vq_qmat *xq, int64_t B, uint8_t *qkv,
+                        uint8_t *ws, hipStream_t stream) {
+    if (!d->qk_gamma) {
+        LinearExtra ex;
+        block_qkv_extra(d, L, B, qkv, ex);
+        return run_linear(xq, d->s_x, &d->w_qkv, d->sw_qkv, 1, d->b_qkv, 0, nullptr, nullptr, 0.0f, nullptr, &ex,
+                          stream, d->wp_qkv);
+    }
+    float *y3 = reinterpret_cast<float *>(ws + L.y3_off);
+    vq_status st = run_linear(xq, d->s_x, &d->w_qkv, d->sw_qkv, 1, d->b_qkv, 0, nullptr, y3, 0.0f, nullptr,
+                              nullptr, stream, d->wp_qkv);
+    if (st != VQ_OK) return st;
+    HeadNormParams hp{};
+    hp.y = y3; hp.ld = 3 * (int64_t)d->D; hp.B = (int)B; hp.H = d->H; hp.N = d->N; hp.D = d->D;
+    hp.gamma = d->qk_gamma; hp.beta = d->qk_beta; hp.eps = d->qk_eps;
+    hp.s_q = d->s_q; hp.s_k = d->s_k; hp.s_v = d->s_v;
+    hp.out = qkv; hp.sb = L.sa; hp.qmin = -(1 << (d->bits_a - 1)); hp.qmax = (1 << (d->bits_a - 1)) - 1;
+    return qkv_headnorm_launch(hp, stream) == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
 // Checks shared by the two block entry points (weights, steps, prepacked copies, dumps).
 vq_status block_args_check(const vq_block_desc *d, const BlockLayout &L, AttnParams *ap) {
     vq_status st;
@@ -430,6 +473,8 @@ vq_status block_args_check(const vq_block_desc *d, const BlockLayout &L, AttnPar
     if (!scaled_alpha(d->s_q, d->s_k, d->scale, L.sa == 4 ? 8 : 0, ap)) return VQ_ERR_STEP;
     for (void *dp : {d->dump_qkv, d->dump_o, d->dump_x2, d->dump_h})
         if (((uintptr_t)dp) % 16 != 0) return VQ_ERR_STRIDE;
+    if ((d->qk_gamma == nullptr) != (d->qk_beta == nullptr)) return VQ_ERR_NULL;
+    if (d->qk_gamma && (!(d->qk_eps >= 0.0f) || !isfinite(d->qk_eps))) return VQ_ERR_STEP;
     const int have = (d->wp_qkv != nullptr) + (d->wp_proj != nullptr) + (d->wp_fc1 != nullptr) +
                      (d->wp_fc2 != nullptr);
     if (have != 0 && have != (d->hidden ? 4 : 2)) return VQ_ERR_NULL;
@@ -479,10 +524,7 @@ vq_status vq_attention_block(const vq_block_desc *d, const vq_qmat *xq, int64_t 
     };
     mark();
     // 1. QKV linear; the epilogue requantizes Q, K, V with their own steps, head-major
-    LinearExtra ex;
-    block_qkv_extra(d, L, B, qkv, ex);
-    st = run_linear(xq, d->s_x, &d->w_qkv, d->sw_qkv, 1, d->b_qkv, 0, nullptr, nullptr, 0.0f, nullptr, &ex,
-                    stream, d->wp_qkv);
+    st = run_qkv_stage(d, L, xq, B, qkv, ws, stream);
     if (st != VQ_OK) return st;
     mark();
 
@@ -584,10 +626,7 @@ vq_status vq_vit_block(const vq_preln_desc *desc, const float *x, int64_t B, flo
     // 1. X_q = LayerNorm-1 quantizer of the stream
     if ((st = lnq(x, desc->ln1_gamma, desc->ln1_beta, d->s_x, xq)) != VQ_OK) return st;
     // 2. QKV linear, fused attention
-    LinearExtra ex;
-    block_qkv_extra(d, L, B, qkv, ex);
-    st = run_linear(&xq, d->s_x, &d->w_qkv, d->sw_qkv, 1, d->b_qkv, 0, nullptr, nullptr, 0.0f, nullptr, &ex,
-                    stream, d->wp_qkv);
+    st = run_qkv_stage(d, L, &xq, B, qkv, ws, stream);
     if (st != VQ_OK) return st;
     {
         AttnParams p;

@@ -204,7 +204,111 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_quantize_kernel(LnParams
     }
 }
 
+// ---- per-head LayerNorm quantizer of Q and K, plain quantizer of V (Fig. 1(b), Table I) --------
+// One lane owns one (token, head) group of 64 channels: it loads the 256 bytes once, runs Eq. 5
+// over them and decides the 64 levels from registers (same guess-and-verify use of the
+// comparator as above; the lanes are independent, so each stops stepping on its own), then
+// writes the head-major packed row the attention kernel reads.  Groups are independent:
+// M * 3H lanes of parallelism, no LDS.
+template <int SB>
+__global__ __launch_bounds__(256) void qkv_headnorm_kernel(HeadNormParams p) {
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int groups = 3 * p.H;
+    const int64_t M = (int64_t)p.B * p.N;
+    if (t >= M * groups) return;
+    const int64_t m = t / groups;
+    const int gi = (int)(t - m * groups);
+    const int which = gi / p.H, h = gi - which * p.H;
+    const int b = (int)(m / p.N), n = (int)(m - (int64_t)b * p.N);
+    const float *src = p.y + m * p.ld + (int64_t)gi * 64;
+    float v[64];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const float4 a = *reinterpret_cast<const float4 *>(src + 4 * q);
+        v[4 * q] = a.x; v[4 * q + 1] = a.y; v[4 * q + 2] = a.z; v[4 * q + 3] = a.w;
+    }
+    const float qminf = (float)p.qmin, qmaxf = (float)p.qmax;
+    float lv[64];
+    if (which == 2) {
+#pragma unroll
+        for (int i = 0; i < 64; ++i) lv[i] = (float)quantize_level(v[i], p.s_v, qminf, qmaxf);
+    } else {
+        float mu = 0.0f, m2 = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 64; ++i) {
+            const float d1 = v[i] - mu;
+            mu = mu + d1 / (float)(i + 1);
+            const float d2 = v[i] - mu;
+            const float pr = d1 * d2;
+            m2 = m2 + pr;
+        }
+        const float nf = 64.0f;
+        const float ne = nf * p.eps;
+        const float V = m2 + ne;
+        const float step = which == 0 ? p.s_q : p.s_k;
+        const float rs = __builtin_amdgcn_rsqf(V / nf);          // for the guess only
+        const float rstep = __builtin_amdgcn_rcpf(step);         // for the guess only
+        const int span = p.qmax - p.qmin;
+        const float *gp = p.gamma + which * p.D + h * 64, *bp = p.beta + which * p.D + h * 64;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const float4 g4 = *reinterpret_cast<const float4 *>(gp + 4 * q);
+            const float4 b4 = *reinterpret_cast<const float4 *>(bp + 4 * q);
+            const float gm[4] = {g4.x, g4.y, g4.z, g4.w}, bt[4] = {b4.x, b4.y, b4.z, b4.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float a = v[4 * q + i] - mu;
+                const float g = a * gm[i];
+                const float gs = g * fabsf(g);
+                const float L = gs * nf;
+                auto above = [&](float k) {
+                    const float rk = (k - 0.5f) * step;
+                    const float cc = rk - bt[i];
+                    const float cs = cc * fabsf(cc);
+                    const float R = cs * V;
+                    return L > R;
+                };
+                const float tt = rintf(fmaf(g, rs, bt[i]) * rstep);
+                float c = (tt == tt) ? __builtin_amdgcn_fmed3f(tt, qminf, qmaxf) : qminf;
+                for (int it = 0; it <= span; ++it) {
+                    const bool low_ok = (c <= qminf) || above(c);
+                    const bool high_ok = (c >= qmaxf) || !above(c + 1.0f);
+                    if (low_ok && high_ok) break;
+                    c = c + (!low_ok ? -1.0f : 1.0f);
+                }
+                lv[4 * q + i] = c;
+            }
+        }
+    }
+    const int64_t row = (((int64_t)which * p.B + b) * p.H + h) * p.N + n;
+    uint8_t *dst = p.out + row * (64 * SB / 8);
+    constexpr int PW = 32 / SB;                      // levels per 32-bit word
+#pragma unroll
+    for (int w4 = 0; w4 < 64 / PW / 4; ++w4) {
+        u32 w[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            u32 acc = 0;
+#pragma unroll
+            for (int i = 0; i < PW; ++i)
+                acc |= ((u32)(int)lv[(4 * w4 + j) * PW + i] & ((1u << SB) - 1u)) << (i * SB);
+            w[j] = acc;
+        }
+        *reinterpret_cast<uint4 *>(dst + 16 * w4) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
 }  // namespace
+
+hipError_t qkv_headnorm_launch(const HeadNormParams &p, hipStream_t stream) {
+    const int64_t threads = (int64_t)p.B * p.N * 3 * p.H;
+    if (threads == 0) return hipSuccess;
+    const unsigned blocks = (unsigned)((threads + 255) / 256);
+    if (p.sb == 4) hipLaunchKernelGGL(qkv_headnorm_kernel<4>, dim3(blocks), dim3(256), 0, stream, p);
+    else if (p.sb == 8) hipLaunchKernelGGL(qkv_headnorm_kernel<8>, dim3(blocks), dim3(256), 0, stream, p);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
 
 hipError_t layernorm_quantize_launch(const LnParams &p, hipStream_t stream) {
     if (p.rows == 0) return hipSuccess;

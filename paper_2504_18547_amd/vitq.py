@@ -18,7 +18,7 @@ STATUS_NAMES = ["VQ_OK", "VQ_ERR_NULL", "VQ_ERR_SHAPE", "VQ_ERR_BITS", "VQ_ERR_S
 EXPORTS = ["vq_status_string", "vq_weight_steps", "vq_quantize", "vq_linear", "vq_matmul_qk",
            "vq_matmul_pv", "vq_attention_block_workspace", "vq_attention_block",
            "vq_prepack_weight_bytes", "vq_prepack_weight", "vq_linear_prepacked", "vq_layernorm_quantize",
-           "vq_vit_block_workspace", "vq_vit_block"]
+           "vq_vit_block_workspace", "vq_vit_block", "vq_qkv_headnorm"]
 
 
 class VitqError(RuntimeError):
@@ -48,7 +48,8 @@ class vq_block_desc(C.Structure):
                 ("dump_qkv", C.c_void_p), ("dump_o", C.c_void_p), ("dump_x2", C.c_void_p),
                 ("dump_h", C.c_void_p), ("stage_events", C.POINTER(C.c_void_p)),
                 ("wp_qkv", C.c_void_p), ("wp_proj", C.c_void_p), ("wp_fc1", C.c_void_p),
-                ("wp_fc2", C.c_void_p)]
+                ("wp_fc2", C.c_void_p), ("qk_gamma", C.c_void_p), ("qk_beta", C.c_void_p),
+                ("qk_eps", C.c_float), ("reserved2", C.c_int32)]
 
 
 class vq_preln_desc(C.Structure):
@@ -88,6 +89,8 @@ def lib():
                                              C.c_float, qp, vp]
         _lib.vq_layernorm_quantize.argtypes = [vp, vp, vp, C.c_int64, C.c_int64, C.c_int64, vp, vp, C.c_float,
                                                C.c_float, qp, vp]
+        _lib.vq_qkv_headnorm.argtypes = [vp, C.c_int64, C.c_int32, C.c_int32, C.c_int32, vp, vp, C.c_float,
+                                         C.c_float, C.c_float, C.c_float, C.c_int32, C.c_int32, vp, vp]
         _lib.vq_vit_block_workspace.argtypes = [C.POINTER(vq_preln_desc), C.c_int64, C.POINTER(C.c_size_t)]
         _lib.vq_vit_block.argtypes = [C.POINTER(vq_preln_desc), vp, C.c_int64, vp, vp, C.c_size_t, vp]
         for n in EXPORTS[1:]:
@@ -210,8 +213,15 @@ def vq_matmul_pv(p, v, B, H, N, s_p, s_v, o_acc_out, o_out, s_o, oq_out):
                               float(s_o), _q(oq_out), _stream()), "vq_matmul_pv")
 
 
-def make_block_desc(dims, bits_a, bits_p, storage_a, weights, steps, dumps=None):
-    """weights: dict name -> QMat (w_*) / fp32 tensors (sw_*, b_*); steps: dict of floats."""
+def vq_qkv_headnorm(y, B, H, N, gamma, beta, eps, s_q, s_k, s_v, bits, storage_bits, out):
+    _check(lib().vq_qkv_headnorm(_ptr(y), y.stride(0), B, H, N, _ptr(gamma), _ptr(beta), float(eps), float(s_q),
+                                 float(s_k), float(s_v), bits, storage_bits, _ptr(out), _stream()),
+           "vq_qkv_headnorm")
+
+
+def make_block_desc(dims, bits_a, bits_p, storage_a, weights, steps, dumps=None, qkln=None):
+    """weights: dict name -> QMat (w_*) / fp32 tensors (sw_*, b_*); steps: dict of floats;
+    qkln: None or dict(gamma, beta device tensors [2D], eps) for the per-head LayerNorm of Q and K."""
     d = vq_block_desc()
     d.D, d.H, d.N, d.hidden = dims["D"], dims["H"], dims["N"], dims.get("hidden", 0)
     d.bits_a, d.bits_p, d.storage_a = bits_a, bits_p, storage_a
@@ -230,6 +240,8 @@ def make_block_desc(dims, bits_a, bits_p, storage_a, weights, steps, dumps=None)
         t = weights.get("wp_" + name)
         if t is not None:
             setattr(d, "wp_" + name, t.data_ptr())
+    if qkln is not None:
+        d.qk_gamma, d.qk_beta, d.qk_eps = qkln["gamma"].data_ptr(), qkln["beta"].data_ptr(), float(qkln["eps"])
     return d
 
 

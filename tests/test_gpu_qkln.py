@@ -1,0 +1,118 @@
+"""GPU parity of the Q/K-LayerNorm attention topology (Fig. 1(b), Table I): vq_qkv_headnorm alone and
+inside vq_attention_block / vq_vit_block, against the CPU oracle -- all levels byte-identical."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from oracle import vqo
+from paper_2504_18547_amd import vitq, workloads as wl
+from tests.gpu_util import assert_fp32_close, dev, device_weights, preln_case, quantized_weights, storage_of
+
+
+def _ln(D, seed=99):
+    rng = np.random.default_rng(seed)
+    return dict(gamma=(1 + 0.1 * rng.standard_normal(2 * D)).astype(np.float32),
+                beta=(0.05 * rng.standard_normal(2 * D)).astype(np.float32), eps=np.float32(1e-6))
+
+
+@pytest.mark.parametrize("bits,B,H,N", [(4, 2, 6, 198), (8, 1, 2, 37), (3, 3, 1, 5), (4, 1, 12, 1)])
+def test_qkv_headnorm_op(bits, B, H, N):
+    rng = np.random.default_rng(bits * 100 + N)
+    D = 64 * H
+    M = B * N
+    y = (rng.standard_normal((M, 3 * D)) * rng.uniform(0.1, 3, (M, 1)) + rng.uniform(-1, 1, (M, 1))).astype(np.float32)
+    y[0, :64] = 2.5                                      # a constant head
+    if M > 2:
+        y[2, 70] = np.inf
+        y[1, 3 * D - 1] = np.nan
+    ln = _ln(D)
+    ln["gamma"][::5] *= -1
+    lo, hi = vqo.qrange(bits)
+    s_q, s_k, s_v = np.float32(3.0 / hi), np.float32(2.5 / hi), np.float32(4.0 / hi)
+    sa = storage_of(bits)
+    out = torch.full((3 * B * H * N, 64 * sa // 8), 0xFF, dtype=torch.uint8, device="cuda")
+    vitq.vq_qkv_headnorm(dev(y), B, H, N, dev(ln["gamma"]), dev(ln["beta"]), ln["eps"], s_q, s_k, s_v, bits, sa, out)
+    torch.cuda.synchronize()
+    got = vqo.unpack(out.cpu().numpy(), 64, sa).reshape(3, B, H, N, 64)
+    for which, step in ((0, s_q), (1, s_k)):
+        for h in range(H):
+            sl = slice(which * D + h * 64, which * D + (h + 1) * 64)
+            ref = vqo.layernorm_quantize(y[:, sl], ln["gamma"][sl], ln["beta"][sl], ln["eps"], step, bits)["q"]
+            assert np.array_equal(got[which][:, h].reshape(M, 64), ref.reshape(B, N, 64).reshape(M, 64)), (which, h)
+    vref = vqo.quantize(np.nan_to_num(y[:, 2 * D:], nan=0.0) if False else y[:, 2 * D:], s_v, bits)
+    assert np.array_equal(got[2].transpose(0, 2, 1, 3).reshape(M, D), vref)
+
+
+def _block(name, images, bits_w, bits_a, prepack=False):
+    dims = wl.block_dims(name)
+    D, H, N, hidden = dims["D"], dims["H"], dims["N"], dims["hidden"]
+    B = len(images)
+    sa = storage_of(bits_a)
+    lo, hi = vqo.qrange(bits_a)
+    st = dict(wl.block_steps(name, True, bits_w, bits_a))
+    st["s_q"] = st["s_k"] = np.float32(3.0 / hi)
+    wts = quantized_weights(wl.block_weights(name, sharp=True), bits_w)
+    wd = device_weights(wts, bits_w, prepack=prepack)
+    ln = _ln(D)
+    tokens = wl.block_tokens(name, images).reshape(B * N, D)
+    xq_ref = vqo.quantize(tokens, st["s_x"], bits_a)
+    xq = vitq.QMat.empty(B * N, D, bits_a)
+    vitq.vq_quantize(dev(tokens), st["s_x"], None, xq)
+    dump = {"qkv": torch.zeros((3 * B * H * N, 64 * sa // 8), dtype=torch.uint8, device="cuda"),
+            "o": torch.zeros((B * N, D * sa // 8), dtype=torch.uint8, device="cuda")}
+    lnd = dict(gamma=dev(ln["gamma"]), beta=dev(ln["beta"]), eps=ln["eps"])
+    desc = vitq.make_block_desc(dims, bits_a, bits_a, sa, wd, st, dump, qkln=lnd)
+    ws = torch.empty(vitq.vq_attention_block_workspace(desc, B), dtype=torch.uint8, device="cuda")
+    y = torch.full((B * N, D), -9.0, dtype=torch.float32, device="cuda")
+    vitq.vq_attention_block(desc, xq, B, y, ws)
+    torch.cuda.synchronize()
+    ref = vqo.attention_block(xq_ref, B, dims, wts, st, bits_a=bits_a, bits_p=bits_a, qkln=ln)
+    qkv = vqo.unpack(dump["qkv"].cpu().numpy(), 64, sa).reshape(3, B, H, N, 64)
+    for i, nm in enumerate("qkv"):
+        assert np.array_equal(qkv[i], ref[nm]), "%s: %s levels differ (%d)" % (name, nm, (qkv[i] != ref[nm]).sum())
+    assert np.array_equal(vqo.unpack(dump["o"].cpu().numpy(), D, sa), ref["o"])
+    assert_fp32_close(y.cpu().numpy(), ref["y"], name + " y")
+    assert np.array_equal(y.cpu().numpy(), ref["y"])
+    return ref
+
+
+def test_table1_head_shape_n198():
+    ref = _block("deit_s_table1", [0, 1], 4, 4)
+    assert len(np.unique(ref["o"])) >= 4
+
+
+@pytest.mark.parametrize("name,bits_w,bits_a,prepack", [("tiny_attn", 4, 4, False), ("tiny_block", 4, 4, True),
+                                                        ("tiny_block", 8, 8, False), ("tiny_attn", 2, 4, False)])
+def test_small_blocks(name, bits_w, bits_a, prepack):
+    _block(name, list(range(wl.BLOCKS[name]["batch"])), bits_w, bits_a, prepack)
+
+
+def test_vit_b_block_reduced_batch():
+    _block("vit_b_block", [0, 1, 2], 4, 4)
+
+
+def test_preln_block_with_qk_layernorm():
+    c = preln_case("tiny_block", True, 4, 4, [0, 1])
+    dims, st, wts, ln, x = c["dims"], dict(c["st"]), c["wts"], c["ln"], c["x"]
+    st["s_q"] = st["s_k"] = np.float32(3.0 / 7)
+    D, N = dims["D"], dims["N"]
+    qk = _ln(D, seed=5)
+    wd = device_weights(wts, 4)
+    qkd = dict(gamma=dev(qk["gamma"]), beta=dev(qk["beta"]), eps=qk["eps"])     # (kept alive: the descriptor holds raw pointers)
+    blk = vitq.make_block_desc(dims, 4, 4, 4, wd, st, qkln=qkd)
+    lnd = {k: dev(v) for k, v in ln.items() if k != "eps"}
+    lnd["eps"] = ln["eps"]
+    desc = vitq.make_preln_desc(blk, lnd)
+    ws = torch.empty(vitq.vq_vit_block_workspace(desc, 2), dtype=torch.uint8, device="cuda")
+    y = torch.zeros((2 * N, D), dtype=torch.float32, device="cuda")
+    vitq.vq_vit_block(desc, dev(x), 2, y, ws)
+    torch.cuda.synchronize()
+    # the oracle chain by hand: LNQ1, attention with Q/K LayerNorm (fp32 out), +x, LNQ2, MLP, +x1
+    xq = vqo.layernorm_quantize(x, ln["g1"], ln["b1"], ln["eps"], st["s_x"], 4)["q"]
+    att = vqo.attention_block(xq, 2, dict(dims, hidden=0), wts, st, qkln=qk)
+    l2 = vqo.layernorm_quantize(att["y"], ln["g2"], ln["b2"], ln["eps"], st["s_x2"], 4, res=x, want_sum=True)
+    h = vqo.linear(l2["q"], st["s_x2"], wts["w_fc1"], wts["sw_fc1"], bias=wts["b_fc1"], act=1, s_y=st["s_h"], bits_y=4)["yq"]
+    t = vqo.linear(h, st["s_h"], wts["w_fc2"], wts["sw_fc2"], bias=wts["b_fc2"])["y"]
+    assert np.array_equal(y.cpu().numpy(), t + l2["sum"])
