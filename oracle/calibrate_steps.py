@@ -6,7 +6,8 @@ quantizer, measured while a few images run through the CPU oracle stage by stage
 tensor gets step 1).  Only oracle/ and the seeded input generators are used.  The resulting
 numbers are plain inputs to both the oracle and the GPU library.
 
-Run:  python -m oracle.calibrate_steps
+Run:  python -m oracle.calibrate_steps            (every workload)
+      python -m oracle.calibrate_steps NAME ...   (only these workloads; the other entries are kept)
 """
 import json
 import os
@@ -24,6 +25,7 @@ VARIANTS = [
     # (workload, images used, [(bits_w, bits_a)])
     ("tiny_attn", [0, 1, 2], [(4, 4), (8, 8), (2, 4), (3, 4)]),
     ("tiny_block", [0, 1], [(4, 4), (8, 8), (2, 4), (3, 4)]),
+    ("tiny_long", [0, 1], [(4, 4), (8, 8)]),
     ("deit_s_table1", [0], [(4, 4), (3, 4)]),
     ("vit_s_attn", [0, 1], [(4, 4)]),
     ("vit_b_block_b128", [0, 1], [(4, 4)]),
@@ -83,7 +85,13 @@ def calibrate(name, images, sharp, bits_w, bits_a):
 
 def main():
     table = {}
+    only = set(sys.argv[1:])
+    if only and os.path.exists(wl.STEPS_FILE):
+        with open(wl.STEPS_FILE) as f:
+            table = json.load(f)
     for name, images, combos in VARIANTS:
+        if only and name not in only:
+            continue
         for bits_w, bits_a in combos:
             for sharp in (False, True):
                 st, info = calibrate(name, images, sharp, bits_w, bits_a)

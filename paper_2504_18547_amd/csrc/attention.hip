@@ -452,10 +452,325 @@ hipError_t launch_mode(const AttnParams &p, AttnMode mode, hipStream_t stream) {
     return hipErrorInvalidValue;
 }
 
+// ---- fused attention, streaming form --------------------------------------------------------
+// The kernel above keeps a whole score row block (16 queries x all keys) in registers, which
+// costs 4 registers per key tile and limits it to one or two waves per SIMD.  The matrix cores
+// are nearly idle in this kernel (the work is the softmax arithmetic), so this form RECOMPUTES
+// the 16x16 score tiles instead of keeping them: pass A takes the integer row maximum (and
+// minimum when the exponential table was cut), pass B the integer sum of the exponentials, pass C
+// quantizes each tile to P levels and feeds the P.V matrix cores one 64-key chunk at a time.
+// Every value is produced by the same arithmetic as above (integer max and sum, table / exact
+// exponential, guarded fp32 quantizer with the 64-bit fallback), so the results are identical;
+// only a handful of registers hold scores at any time, and the key count is a run-time value.
+constexpr int kStreamThreads = 512;     // 8 waves share one head's K / V^T in LDS
+
+template <int SB, bool P8, bool LUT>
+__global__ __launch_bounds__(kStreamThreads, 2) void attention_stream_kernel(AttnParams p) {
+    constexpr int NTHR = kStreamThreads, NW = NTHR / 64;
+    constexpr int KROW = 64 * SB / 8;
+    constexpr int KPITCH = (SB == 4) ? 40 : 80;
+    constexpr int SHIFT = (SB == 4) ? 8 : 0;
+    const int N = p.N;
+    const int nt = (N + 15) / 16;                     // key tiles
+    const int nch = (nt + 3) / 4;                     // 64-key chunks
+    const int nkeyp = nch * 64;
+    const int vpitch = nkeyp + 16;
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    uint8_t *sK = smem;                               // [nch*64][KPITCH] (rows >= N are zero)
+    uint8_t *sVT = smem + (((size_t)nkeyp * KPITCH + 15) & ~(size_t)15);   // [64][vpitch] int8
+    u32 *sLUT = reinterpret_cast<u32 *>(sVT + 64 * vpitch);
+    const int lut_last = p.lut_n - 1;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int li = lane & 15;
+    const int g = lane >> 4;
+    const int bh = blockIdx.x;
+    const int b = bh / p.H;
+    const int h = bh - b * p.H;
+    const int64_t row0 = (int64_t)bh * N;
+
+    if constexpr (LUT) {
+        for (int i = tid; i < p.lut_n; i += NTHR)
+            sLUT[i] = (i == lut_last) ? 0u : shift_exp_fixed(-i, p.alpha);
+    }
+    {
+        constexpr int CH = KROW / 8;
+        for (int id = tid; id < nkeyp * CH; id += NTHR) {
+            int n = id / CH, c = id - n * CH;
+            uint2 v = make_uint2(0, 0);
+            if (n < N) v = *reinterpret_cast<const uint2 *>(p.k + (row0 + n) * p.k_stride + c * 8);
+            *reinterpret_cast<uint2 *>(sK + n * KPITCH + c * 8) = v;
+        }
+    }
+    {
+        constexpr int CH = KROW / 16;
+        for (int id = tid; id < nkeyp * CH; id += NTHR) {
+            int n = id / CH, c = id - n * CH;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (n < N) v = *reinterpret_cast<const uint4 *>(p.v + (row0 + n) * p.v_stride + c * 16);
+            const u32 w[4] = {v.x, v.y, v.z, v.w};
+            const int pos = vt_pos(n);
+            if constexpr (SB == 4) {
+#pragma unroll
+                for (int j = 0; j < 32; ++j) {
+                    int val = ((int)(w[j >> 3] << (28 - 4 * (j & 7)))) >> 28;
+                    sVT[vt_row(32 * c + j) * vpitch + pos] = (uint8_t)val;
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 16; ++j)
+                    sVT[vt_row(16 * c + j) * vpitch + pos] = (uint8_t)(w[j >> 2] >> (8 * (j & 3)));
+            }
+        }
+    }
+    __syncthreads();
+
+    const int nqb = (N + 15) / 16;
+    const int wslot = (wave + bh) % NW;
+    const float thr_p = 0.5f - (P8 ? 0x1p-13f : 0x1p-17f);
+    const u32 two_pmax = 2u * (u32)p.pmax;
+    for (int qb = blockIdx.y * NW + wslot; qb < nqb; qb += NW * p.qsplit) {
+        const int qrow = qb * 16 + li;
+        const bool qok = qrow < N;
+        v4i qf;
+        {
+            const uint8_t *src = p.q + (row0 + qrow) * p.q_stride;
+            if constexpr (SB == 4) {
+                uint2 v = make_uint2(0, 0);
+                if (qok) v = *reinterpret_cast<const uint2 *>(src + 8 * g);
+                qf = unpack4_x16(v.x, v.y);
+            } else {
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (qok) v = *reinterpret_cast<const uint4 *>(src + 16 * g);
+                qf[0] = (int)v.x; qf[1] = (int)v.y; qf[2] = (int)v.z; qf[3] = (int)v.w;
+            }
+        }
+        // one 16-key tile of S^T: lane (query li, group g) gets keys 16t + 4g + r
+        auto score_tile = [&](int t) -> v4i {
+            v4i kf;
+            const uint8_t *src = sK + (16 * t + li) * KPITCH;
+            if constexpr (SB == 4) {
+                uint2 v = *reinterpret_cast<const uint2 *>(src + 8 * g);
+                kf = unpack4_x16(v.x, v.y);
+            } else {
+                kf = *reinterpret_cast<const v4i *>(src + 16 * g);
+            }
+            v4i z = {0, 0, 0, 0};
+            return __builtin_amdgcn_mfma_i32_16x16x64_i8(kf, qf, z, 0, 0, 0);
+        };
+        const int nfull = N / 16;                      // tiles [0, nfull) hold only real keys
+
+        // ---- pass A: integer row max (and min) -------------------------------------------------
+        int mx = INT32_MIN, mn = INT32_MAX;
+#pragma unroll 4
+        for (int t = 0; t < nfull; ++t) {
+            const v4i s = score_tile(t);
+            mx = max(mx, max(max(s[0], s[1]), max(s[2], s[3])));
+            if (LUT && !p.lut_full) mn = min(mn, min(min(s[0], s[1]), min(s[2], s[3])));
+        }
+        if (nfull < nt) {
+            const v4i s = score_tile(nfull);
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (16 * nfull + 4 * g + r < N) { mx = max(mx, s[r]); mn = min(mn, s[r]); }
+        }
+        mx = max(mx, __shfl_xor(mx, 16, 64));
+        mx = max(mx, __shfl_xor(mx, 32, 64));
+        bool direct = !LUT;
+        if constexpr (LUT) {
+            if (!p.lut_full) {
+                mn = min(mn, __shfl_xor(mn, 16, 64));
+                mn = min(mn, __shfl_xor(mn, 32, 64));
+                direct = __builtin_amdgcn_ballot_w64(((mx - mn) >> SHIFT) >= lut_last) != 0;
+            }
+        }
+        auto exp_of = [&](int sv) -> u32 {
+            if (LUT && !direct) {
+                constexpr int LSH = SHIFT >= 2 ? SHIFT - 2 : 0;
+                const u32 off = min((u32)(mx - sv) >> LSH, 4u * (u32)lut_last);
+                return *reinterpret_cast<const u32 *>(reinterpret_cast<const uint8_t *>(sLUT) + off);
+            }
+            return shift_exp_fixed(sv - mx, p.alpha_scaled);
+        };
+        // exponentials of one tile, zero for keys >= N
+        auto exp_tile = [&](int t, u32 (&e)[4]) {
+            const v4i s = score_tile(t);
+            if (t < nfull) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) e[r] = exp_of(s[r]);
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) e[r] = (16 * t + 4 * g + r < N) ? exp_of(s[r]) : 0u;
+            }
+        };
+
+        // ---- pass B: integer row sum of the exponentials ---------------------------------------
+        u32 sum = 0;
+#pragma unroll 4
+        for (int t = 0; t < nt; ++t) {
+            u32 e[4];
+            exp_tile(t, e);
+            sum += (e[0] + e[1]) + (e[2] + e[3]);
+        }
+        sum += __shfl_xor(sum, 16, 64);
+        sum += __shfl_xor(sum, 32, 64);
+        const float inv = (float)p.pmax / (float)sum;
+
+        // ---- pass C: P levels, one 64-key chunk at a time, into the P.V matrix cores -----------
+        v4i o[4], cs[4];
+#pragma unroll
+        for (int T = 0; T < 4; ++T) { o[T] = v4i{0, 0, 0, 0}; cs[T] = v4i{0, 0, 0, 0}; }
+        for (int c = 0; c < nch; ++c) {
+            u32 pp[4];
+            float worst = 0.0f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int t = 4 * c + j;
+                u32 packed = 0;
+                if (t < nt) {
+                    u32 e[4];
+                    exp_tile(t, e);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const float x = (float)e[r] * inv;
+                        const float q = rintf(x);
+                        worst = fmaxf(worst, fabsf(x - q));
+                        packed = __builtin_amdgcn_cvt_pk_u8_f32(q, r, packed);
+                    }
+                }
+                pp[j] = P8 ? (packed ^ 0x80808080u) : packed;
+            }
+            if (__builtin_amdgcn_ballot_w64(!(worst <= thr_p)) != 0) {
+                // some ratio of this chunk is within the error bound of a half: decide its levels
+                // in exact 64-bit integer arithmetic (rare)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int t = 4 * c + j;
+                    u32 packed = 0;
+                    if (t < nt) {
+                        u32 e[4];
+                        exp_tile(t, e);
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            u32 lvl = (u32)rintf((float)e[r] * inv);
+                            const uint64_t lhs = (uint64_t)two_pmax * e[r];
+                            const uint64_t up = (uint64_t)(2u * lvl + 1u) * sum;
+                            const uint64_t dn = (uint64_t)(2u * lvl - 1u) * sum;   // only used when lvl > 0
+                            if (lhs > up) lvl += 1;
+                            else if (lvl > 0 && lhs <= dn) lvl -= 1;
+                            lvl = min(lvl, (u32)p.pmax);
+                            packed |= lvl << (8 * r);
+                        }
+                    }
+                    pp[j] = P8 ? (packed ^ 0x80808080u) : packed;
+                }
+            }
+            v4i pf;
+            pf[0] = (int)pp[0]; pf[1] = (int)pp[1]; pf[2] = (int)pp[2]; pf[3] = (int)pp[3];
+#pragma unroll
+            for (int T = 0; T < 4; ++T) {
+                v4i vf = *reinterpret_cast<const v4i *>(sVT + (16 * T + li) * vpitch + 64 * c + 16 * g);
+                o[T] = __builtin_amdgcn_mfma_i32_16x16x64_i8(vf, pf, o[T], 0, 0, 0);
+                if constexpr (P8) {
+                    const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
+                    cs[T] = __builtin_amdgcn_mfma_i32_16x16x64_i8(vf, ones, cs[T], 0, 0, 0);
+                }
+            }
+        }
+
+        // ---- output: scale, requantize (guarded), pack ------------------------------------------
+        if (qok) {
+            float lv[16];
+            float of[16];
+            const float bias8 = -p.qminf, top = p.qmaxf - p.qminf;
+            const float thr_o = 0.5f - p.eps_o;
+            u32 worst_o = 0u;
+#pragma unroll
+            for (int T = 0; T < 4; ++T)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    int a = o[T][r];
+                    if constexpr (P8) a += 128 * cs[T][r];
+                    const float ov = (float)a * p.spv;
+                    of[4 * T + r] = ov;
+                    const float t8 = fmaf(ov, p.r_o, bias8);
+                    const float q8 = rintf(t8);
+                    worst_o = max(worst_o, __float_as_uint(fabsf(t8 - q8)));
+                    lv[4 * T + r] = __builtin_amdgcn_fmed3f(q8, 0.0f, top);
+                }
+            if (__builtin_amdgcn_ballot_w64(worst_o > __float_as_uint(thr_o)) != 0) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    lv[i] = __builtin_amdgcn_fmed3f(rintf(of[i] / p.s_o) + bias8, 0.0f, top);
+            }
+            const int d0 = 16 * g;
+            const int64_t orow = (int64_t)b * N + qrow;
+            uint8_t *dst = p.oq + orow * p.oq_stride + (((h * 64 + d0) * p.oq_sb) >> 3);
+            if (p.oq_sb == 4) {
+                u32 ev0 = 0, od0 = 0, ev1 = 0, od1 = 0;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    ev0 = __builtin_amdgcn_cvt_pk_u8_f32(lv[2 * i], i, ev0);
+                    od0 = __builtin_amdgcn_cvt_pk_u8_f32(lv[2 * i + 1], i, od0);
+                    ev1 = __builtin_amdgcn_cvt_pk_u8_f32(lv[8 + 2 * i], i, ev1);
+                    od1 = __builtin_amdgcn_cvt_pk_u8_f32(lv[8 + 2 * i + 1], i, od1);
+                }
+                const u32 fix = 0x11111111u * ((u32)bias8 & 0xFu);
+                *reinterpret_cast<uint2 *>(dst) = make_uint2(nib_sub(ev0 | (od0 << 4), fix), nib_sub(ev1 | (od1 << 4), fix));
+            } else {
+                const u32 fix = 0x01010101u * ((u32)bias8 & 0xFFu);
+                u32 w[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    u32 v = 0;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) v = __builtin_amdgcn_cvt_pk_u8_f32(lv[4 * j + i], i, v);
+                    w[j] = ((v | 0x80808080u) - (fix & 0x7F7F7F7Fu)) ^ ((v ^ ~fix) & 0x80808080u);
+                }
+                *reinterpret_cast<uint4 *>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
+            }
+        }
+    }
+}
+
+template <int SB, bool P8, bool LUT>
+hipError_t launch_stream(const AttnParams &p, hipStream_t stream) {
+    constexpr int KPITCH = (SB == 4) ? 40 : 80;
+    const int nch = ((p.N + 15) / 16 + 3) / 4;
+    const size_t lds = (((size_t)nch * 64 * KPITCH + 15) & ~(size_t)15) + (size_t)64 * (nch * 64 + 16) +
+                       (LUT ? (size_t)p.lut_n * 4 : 0);
+    auto kern = attention_stream_kernel<SB, P8, LUT>;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    dim3 grid((unsigned)(p.B * p.H), (unsigned)p.qsplit);
+    hipLaunchKernelGGL(kern, grid, dim3(kStreamThreads), lds, stream, p);
+    return hipGetLastError();
+}
+
+template <int SB>
+hipError_t launch_stream_p(const AttnParams &p, hipStream_t stream) {
+    if (p.pmax > 127) return launch_stream<SB, true, false>(p, stream);
+    if (SB == 4 && p.lut_n > 0) return launch_stream<SB, false, true>(p, stream);
+    return launch_stream<SB, false, false>(p, stream);
+}
+
 }  // namespace
 
+#ifndef VITQ_STREAM_MIN_N
+#define VITQ_STREAM_MIN_N 209
+#endif
 hipError_t attention_launch(const AttnParams &p, AttnMode mode, hipStream_t stream) {
     if (p.B * p.H == 0) return hipSuccess;
+    // fused attention with packed output only: long rows take the streaming form
+    if (mode == kAttnFused && p.oq && !p.o_acc_out && !p.o_out && p.N >= VITQ_STREAM_MIN_N && p.N <= 37 * 16) {
+        if (p.sb == 4) return launch_stream_p<4>(p, stream);
+        if (p.sb == 8) return launch_stream_p<8>(p, stream);
+    }
     if (p.N <= 13 * 16) {
         if (p.sb == 4) return launch_mode<13, 4>(p, mode, stream);
         if (p.sb == 8) return launch_mode<13, 8>(p, mode, stream);

@@ -29,6 +29,8 @@ BLOCKS = {
     # small stand-ins used by the parity tests (same recipe, tiny shapes)
     "tiny_attn": dict(cfg=12, D=128, H=2, N=37, hidden=0, batch=3),
     "tiny_block": dict(cfg=13, D=128, H=2, N=50, hidden=256, batch=2),
+    # more than 208 tokens at a tiny width: the long-row form of the attention kernel
+    "tiny_long": dict(cfg=15, D=128, H=2, N=230, hidden=256, batch=2),
     # the paper's own per-head shape (Table I: N=198, I=384, O=64)
     "deit_s_table1": dict(cfg=14, D=384, H=6, N=198, hidden=0, batch=2),
 }

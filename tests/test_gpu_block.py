@@ -74,6 +74,16 @@ def test_tiny_blocks_all_bit_widths(name, sharp, bits_w, bits_a, prepack):
         assert len(np.unique(ref["o"])) >= 5          # the attention output is not degenerate
 
 
+@pytest.mark.parametrize("sharp", [False, True])
+@pytest.mark.parametrize("bits_w,bits_a", [(4, 4), (8, 8)])
+def test_long_rows_take_the_streaming_attention(bits_w, bits_a, sharp):
+    """N = 230 > 208 tokens: the attention runs in its long-row (score-recomputing) form."""
+    out, inp = run_block_gpu("tiny_long", [0, 1], sharp, bits_w, bits_a)
+    ref = compare_with_oracle(out, inp, bits_a, "tiny_long w%da%d" % (bits_w, bits_a))
+    if sharp:
+        assert len(np.unique(ref["o"])) >= 5
+
+
 def test_paper_head_shape_n198():
     """Table I's shape: N = 198 tokens, 384 inputs, 6 heads of 64."""
     out, inp = run_block_gpu("deit_s_table1", [0, 1], True, 4, 4, prepack=True)

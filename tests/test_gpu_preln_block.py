@@ -58,6 +58,10 @@ def test_tiny_block(bits_w, bits_a, prepack, sharp):
     assert np.abs(ref["y"] - ref["x1"]).max() > 0.05
 
 
+def test_long_rows():
+    _run("tiny_long", [0, 1], True, 4, 4)
+
+
 def test_dumps_do_not_change_the_result():
     a, _ = _run("tiny_block", [0, 1], True, 4, 4, dumps=True)
     b, _ = _run("tiny_block", [0, 1], True, 4, 4, dumps=False)

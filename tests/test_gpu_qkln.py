@@ -84,6 +84,7 @@ def test_table1_head_shape_n198():
 
 
 @pytest.mark.parametrize("name,bits_w,bits_a,prepack", [("tiny_attn", 4, 4, False), ("tiny_block", 4, 4, True),
+                                                        ("tiny_long", 4, 4, False),
                                                         ("tiny_block", 8, 8, False), ("tiny_attn", 2, 4, False)])
 def test_small_blocks(name, bits_w, bits_a, prepack):
     _block(name, list(range(wl.BLOCKS[name]["batch"])), bits_w, bits_a, prepack)
