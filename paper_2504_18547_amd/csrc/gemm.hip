@@ -25,6 +25,11 @@ namespace vitq {
 
 namespace {
 
+#ifndef VITQ_BK88
+#define VITQ_BK88 64
+#define VITQ_S88 3
+#define VITQ_OCC88 3
+#endif
 #ifndef VITQ_BK84
 #define VITQ_BK84 128
 #define VITQ_S84 2
@@ -664,7 +669,7 @@ hipError_t gemm_launch(GemmParams p, int wb, int ab, hipStream_t stream) {
     }
     if (wb == 4 && ab == 4) return launch_epi<4, 4, 128, 128, 2, 2, 128, 3, 3>(p, epi, stream);
     if (wb == 2 && ab == 4) return launch_epi<2, 4, 128, 128, 2, 2, 128, 3, 3>(p, epi, stream);
-    if (wb == 8 && ab == 8) return launch_epi<8, 8, 128, 128, 2, 2, 64, 3, 3>(p, epi, stream);
+    if (wb == 8 && ab == 8) return launch_epi<8, 8, 128, 128, 2, 2, VITQ_BK88, VITQ_S88, VITQ_OCC88>(p, epi, stream);
     if (wb == 8 && ab == 4) return launch_epi<8, 4, 128, 128, 2, 2, VITQ_BK84, VITQ_S84, VITQ_OCC84>(p, epi, stream);
     return hipErrorInvalidValue;
 }
