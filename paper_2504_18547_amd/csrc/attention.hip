@@ -18,6 +18,12 @@
 #include "attention.h"
 #include "vitq_dev.h"
 
+#ifndef VITQ_ATT_OCC
+#define VITQ_ATT_OCC 4      // workgroups per CU aimed at by the 4-bit kernels of up to 13 key tiles
+#endif
+#ifndef VITQ_ATT_GROUP
+#define VITQ_ATT_GROUP 2    // key tiles between scheduling fences (bounds the loads in flight, hence registers)
+#endif
 namespace vitq {
 
 namespace {
@@ -48,7 +54,7 @@ __device__ __forceinline__ u32 shift_exp_fixed(int d, float alpha) {
 
 // TAIL: N > 16*(NT-1), i.e. every key tile but the last holds only real keys (no masking there).
 template <int NT, int SB, int MODE, bool P8, bool LUT, bool TAIL>
-__global__ __launch_bounds__(256, (NT <= 13 ? 2 : 1)) void attention_kernel(AttnParams p) {
+__global__ __launch_bounds__(256, (NT <= 13 ? ((SB == 4 && !P8) ? VITQ_ATT_OCC : 2) : 1)) void attention_kernel(AttnParams p) {
     constexpr int NCH = (NT + 3) / 4;                 // 64-key chunks of the P.V contraction
     constexpr int NKEYP = NCH * 64;                   // padded key count of V^T rows
     constexpr int KROW = 64 * SB / 8;                 // bytes of one packed K row
@@ -214,6 +220,8 @@ __global__ __launch_bounds__(256, (NT <= 13 ? 2 : 1)) void attention_kernel(Attn
                 };
                 static_for<NT>([&](auto T) {
                     constexpr int t = decltype(T)::value;
+                    if constexpr (VITQ_ATT_GROUP > 0 && t % (VITQ_ATT_GROUP > 0 ? VITQ_ATT_GROUP : 1) == 0 && t > 0)
+                        __builtin_amdgcn_sched_barrier(0);     // bound the table loads in flight (registers)
                     if (TAIL && t < NT - 1) {
 #pragma unroll
                         for (int r = 0; r < 4; ++r) { const u32 e = exp_of(s[t][r]); s[t][r] = (int)e; sum += e; }
@@ -242,6 +250,8 @@ __global__ __launch_bounds__(256, (NT <= 13 ? 2 : 1)) void attention_kernel(Attn
             float worst = 0.0f;            // largest distance of a ratio from its rounded value
             static_for<NT>([&](auto T) {
                 constexpr int t = decltype(T)::value;
+                if constexpr (VITQ_ATT_GROUP > 0 && t % (VITQ_ATT_GROUP > 0 ? VITQ_ATT_GROUP : 1) == 0 && t > 0)
+                    __builtin_amdgcn_sched_barrier(0);
                 u32 packed = 0;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
