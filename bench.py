@@ -90,6 +90,8 @@ def main():
     ap.add_argument("--batch", type=int, default=0, help="0 = the batch the configuration is quoted on")
     ap.add_argument("--sharp", action="store_true", help="sharp-attention variant of the weights")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true",
+                    help="skip the entry points timed outside the step (keeps a profile to the step's kernels)")
     ap.add_argument("--prepack", action="store_true",
                     help="give the block the expanded int8 weight copies made once by vq_prepack_weight "
                          "instead of letting every GEMM tile unpack the packed weights itself")
@@ -224,66 +226,68 @@ def main():
         "stage_ms": stage_ms,
         "roofline": roofline,
     }
-    # Outside the step (not part of `value`): the LayerNorm + comparator-quantizer glue kernel of
-    # Sec. IV-C on the same token matrix, timed on its own with HIP events.
-    gam = torch.ones(D, device="cuda")
-    bet = torch.zeros(D, device="cuda")
-    lq = vitq.QMat.empty(B * N, D, ba)
-    e0, e1 = hip.event(), hip.event()
-    for i in range(4):
-        if i == 1:
-            hip.record(e0, stream)
-        vitq.vq_layernorm_quantize(tokens, None, None, gam, bet, 1e-5, st["s_x"], lq)
-    hip.record(e1, stream)
-    torch.cuda.synchronize()
-    ln_ms = hip.elapsed_ms(e0, e1) / 3
-    ln_bytes = B * N * D * 4 + B * N * D * sa // 8
-    out["extra"] = {"vq_layernorm_quantize": {"ms": ln_ms, "rows": B * N, "cols": D,
-                                              "algorithmic_gbs": ln_bytes / (ln_ms * 1e-3) / 1e9,
-                                              "note": "not part of the step; fp32 in, packed levels out"}}
-    # Outside the step: the same chain with per-head LayerNorm quantizers on Q and K (the paper's
-    # own attention topology, Table I); nominal steps 3 sigma / qmax for Q and K.
-    qmax_a = float((1 << (ba - 1)) - 1)
-    st3 = dict(st)
-    st3["s_q"] = st3["s_k"] = 3.0 / qmax_a
-    qk_g = torch.ones(2 * D, device="cuda")
-    qk_b = torch.zeros(2 * D, device="cuda")
-    desc3 = vitq.make_block_desc(dims, ba, ba, sa, wd, st3, qkln={"gamma": qk_g, "beta": qk_b, "eps": 1e-6})
-    ws3 = torch.empty(vitq.vq_attention_block_workspace(desc3, B), dtype=torch.uint8, device="cuda")
-    for i in range(4):
-        if i == 1:
-            hip.record(e0, stream)
-        vitq.vq_attention_block(desc3, xq, B, y, ws3)
-    hip.record(e1, stream)
-    torch.cuda.synchronize()
-    qk_ms = hip.elapsed_ms(e0, e1) / 3
-    out["extra"]["vq_attention_block_qk_layernorm"] = {
-        "ms": qk_ms, "images_per_s": B / (qk_ms * 1e-3),
-        "note": "not part of the step; QKV linear in fp32, then vq_qkv_headnorm, then the same stages"}
-    del ws3
-    if hidden:
-        # Also outside the step: the whole pre-LayerNorm block on the fp32 residual stream
-        # (LNQ1 -> attention -> +x -> LNQ2 -> MLP -> +x1), nominal steps for the two LayerNorm
-        # quantizers (3.5 sigma / qmax) and the GELU output.
-        qmax = float((1 << (ba - 1)) - 1)
-        st2 = dict(st)
-        st2["s_x"] = st2["s_x2"] = 3.5 / qmax
-        st2["s_h"] = 2.5 / qmax
-        blk2 = vitq.make_block_desc(dims, ba, ba, sa, wd, st2)
-        ln = {"g1": gam, "b1": bet, "g2": gam, "b2": bet, "eps": 1e-6}
-        pd = vitq.make_preln_desc(blk2, ln)
-        ws2 = torch.empty(vitq.vq_vit_block_workspace(pd, B), dtype=torch.uint8, device="cuda")
+    if not args.no_extra:
+        # Outside the step (not part of `value`): the LayerNorm + comparator-quantizer glue kernel of
+        # Sec. IV-C on the same token matrix, timed on its own with HIP events.
+        gam = torch.ones(D, device="cuda")
+        bet = torch.zeros(D, device="cuda")
+        lq = vitq.QMat.empty(B * N, D, ba)
+        e0, e1 = hip.event(), hip.event()
         for i in range(4):
             if i == 1:
                 hip.record(e0, stream)
-            vitq.vq_vit_block(pd, tokens, B, y, ws2)
+            vitq.vq_layernorm_quantize(tokens, None, None, gam, bet, 1e-5, st["s_x"], lq)
         hip.record(e1, stream)
         torch.cuda.synchronize()
-        pl_ms = hip.elapsed_ms(e0, e1) / 3
-        out["extra"]["vq_vit_block"] = {"ms": pl_ms, "images_per_s": B / (pl_ms * 1e-3),
-                                        "tops": B * ops_img / (pl_ms * 1e-3) / 1e12,
-                                        "note": "not part of the step; fp32 stream in and out, two LayerNorm "
-                                                "quantizers and both residual adds included"}
+        ln_ms = hip.elapsed_ms(e0, e1) / 3
+        ln_bytes = B * N * D * 4 + B * N * D * sa // 8
+        out["extra"] = {"vq_layernorm_quantize": {"ms": ln_ms, "rows": B * N, "cols": D,
+                                                  "algorithmic_gbs": ln_bytes / (ln_ms * 1e-3) / 1e9,
+                                                  "note": "not part of the step; fp32 in, packed levels out"}}
+        # Outside the step: the same chain with per-head LayerNorm quantizers on Q and K (the paper's
+        # own attention topology, Table I); nominal steps 3 sigma / qmax for Q and K.
+        qmax_a = float((1 << (ba - 1)) - 1)
+        st3 = dict(st)
+        st3["s_q"] = st3["s_k"] = 3.0 / qmax_a
+        qk_g = torch.ones(2 * D, device="cuda")
+        qk_b = torch.zeros(2 * D, device="cuda")
+        desc3 = vitq.make_block_desc(dims, ba, ba, sa, wd, st3, qkln={"gamma": qk_g, "beta": qk_b, "eps": 1e-6})
+        ws3 = torch.empty(vitq.vq_attention_block_workspace(desc3, B), dtype=torch.uint8, device="cuda")
+        for i in range(4):
+            if i == 1:
+                hip.record(e0, stream)
+            vitq.vq_attention_block(desc3, xq, B, y, ws3)
+        hip.record(e1, stream)
+        torch.cuda.synchronize()
+        qk_ms = hip.elapsed_ms(e0, e1) / 3
+        out["extra"]["vq_attention_block_qk_layernorm"] = {
+            "ms": qk_ms, "images_per_s": B / (qk_ms * 1e-3),
+            "note": "not part of the step; per-head LayerNorm quantizers of Q and K inside the QKV epilogue, "
+                    "then the same stages"}
+        del ws3
+        if hidden:
+            # Also outside the step: the whole pre-LayerNorm block on the fp32 residual stream
+            # (LNQ1 -> attention -> +x -> LNQ2 -> MLP -> +x1), nominal steps for the two LayerNorm
+            # quantizers (3.5 sigma / qmax) and the GELU output.
+            qmax = float((1 << (ba - 1)) - 1)
+            st2 = dict(st)
+            st2["s_x"] = st2["s_x2"] = 3.5 / qmax
+            st2["s_h"] = 2.5 / qmax
+            blk2 = vitq.make_block_desc(dims, ba, ba, sa, wd, st2)
+            ln = {"g1": gam, "b1": bet, "g2": gam, "b2": bet, "eps": 1e-6}
+            pd = vitq.make_preln_desc(blk2, ln)
+            ws2 = torch.empty(vitq.vq_vit_block_workspace(pd, B), dtype=torch.uint8, device="cuda")
+            for i in range(4):
+                if i == 1:
+                    hip.record(e0, stream)
+                vitq.vq_vit_block(pd, tokens, B, y, ws2)
+            hip.record(e1, stream)
+            torch.cuda.synchronize()
+            pl_ms = hip.elapsed_ms(e0, e1) / 3
+            out["extra"]["vq_vit_block"] = {"ms": pl_ms, "images_per_s": B / (pl_ms * 1e-3),
+                                            "tops": B * ops_img / (pl_ms * 1e-3) / 1e12,
+                                            "note": "not part of the step; fp32 stream in and out, two LayerNorm "
+                                                    "quantizers and both residual adds included"}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(name, args.sharp, bw, ba, ops_img)
     print(json.dumps(out))

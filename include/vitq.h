@@ -169,9 +169,11 @@ typedef struct vq_block_desc {
     const void *wp_qkv, *wp_proj, *wp_fc1, *wp_fc2;
     /* Optional per-head LayerNorm of Q and K (Fig. 1(b), Table I: a LayerNorm of 2 x O elements
      * after the Q and the K linear, none after V).  qk_gamma, qk_beta: device fp32 [2D] (Q
-     * channels, then K channels), nullable together.  When given, the QKV linear writes fp32
-     * into the workspace and vq_qkv_headnorm turns it into the packed Q, K, V: s_q and s_k are
-     * then the steps of the two LayerNorm quantizers, and the scalar s_x is cancelled by them.  */
+     * channels, then K channels), nullable together.  When given, s_q and s_k are the steps of
+     * the two LayerNorm quantizers (the scalar s_x is cancelled by them); the packed Q, K, V
+     * are those of the QKV linear in fp32 followed by vq_qkv_headnorm.  The quantizers run in
+     * the linear's epilogue (the fp32 values stay in registers) unless 1/s_q, 1/s_k or 1/s_v
+     * leaves [2^-100, 2^100]: then the fp32 matrix goes through the workspace.              */
     const float *qk_gamma, *qk_beta;
     float qk_eps;
     int32_t reserved2;

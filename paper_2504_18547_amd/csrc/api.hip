@@ -46,6 +46,7 @@ struct LinearExtra {      // head-major output of the QKV linear inside the bloc
     int D = 0, dh = 0, Ntok = 0, Bimg = 0, Hh = 0;
     float s_q = 0, s_k = 0, s_v = 0;
     uint8_t *dst = nullptr; int sb = 0; int bits = 0;
+    const float *hn_gamma = nullptr, *hn_beta = nullptr; float hn_eps = 0;   // per-head LayerNorm on Q, K
 };
 
 // Shared by vq_linear and vq_attention_block; all descriptors already validated.
@@ -67,6 +68,7 @@ vq_status run_linear(const vq_qmat *xq, float s_x, const vq_qmat *wq, const floa
         p.head_major = 1;
         p.D = ex->D; p.dh = ex->dh; p.Ntok = ex->Ntok; p.Bimg = ex->Bimg; p.Hh = ex->Hh;
         p.s_y[0] = ex->s_q; p.s_y[1] = ex->s_k; p.s_y[2] = ex->s_v;
+        p.hn_gamma = ex->hn_gamma; p.hn_beta = ex->hn_beta; p.hn_eps = ex->hn_eps;
         p.yq = ex->dst; p.yq_sb = ex->sb; p.yq_stride = (int64_t)ex->dh * ex->sb / 8;
         p.yq_row_bytes16 = (int)p.yq_stride;
         level_range(ex->bits, &p.qminf, &p.qmaxf);
@@ -435,13 +437,19 @@ void block_attention_params(const vq_block_desc *d, const BlockLayout &L, const 
     p.r_o = 1.0f / p.s_o; p.eps_o = ldexpf(1.0f, (p.qmaxf > 7.5f ? 8 : 4) - 22);
 }
 
-// QKV stage of both block entry points: the linear with the head-major requantizing epilogue, or,
-// with the per-head LayerNorm of Q and K, the linear in fp32 followed by vq_qkv_headnorm's kernel.
+// QKV stage of both block entry points: the linear with the head-major requantizing epilogue
+// (plain quantizers, or the per-head LayerNorm quantizers of Q and K inside that epilogue), or,
+// for steps the fused epilogue does not take, the linear in fp32 and then vq_qkv_headnorm's kernel.
 vq_status run_qkv_stage(const vq_block_desc *d, const BlockLayout &L, const vq_qmat *xq, int64_t B, uint8_t *qkv,
                         uint8_t *ws, hipStream_t stream) {
-    if (!d->qk_gamma) {
+    // With 64-channel heads the per-head LayerNorm quantizers run inside the linear's epilogue
+    // (its fast paths need steps whose reciprocals are ordinary numbers).
+    auto ordinary = [](float s) { const float r = 1.0f / s; return r > 0x1p-100f && r < 0x1p100f; };
+    const bool fused_norm = d->qk_gamma && d->D % 64 == 0 && ordinary(d->s_q) && ordinary(d->s_k) && ordinary(d->s_v);
+    if (!d->qk_gamma || fused_norm) {
         LinearExtra ex;
         block_qkv_extra(d, L, B, qkv, ex);
+        if (fused_norm) { ex.hn_gamma = d->qk_gamma; ex.hn_beta = d->qk_beta; ex.hn_eps = d->qk_eps; }
         return run_linear(xq, d->s_x, &d->w_qkv, d->sw_qkv, 1, d->b_qkv, 0, nullptr, nullptr, 0.0f, nullptr, &ex,
                           stream, d->wp_qkv);
     }

@@ -23,6 +23,10 @@ struct GemmParams {
     // head-major output of the QKV linear: channel -> (q/k/v, head, d), token -> (image, n)
     int head_major; int D, dh, Ntok, Bimg, Hh;
     int dh_shift; float inv_ntok;                    // filled by gemm_launch
+    // per-head LayerNorm quantizers on Q and K inside the head-major epilogue (Sec. IV-C): gamma
+    // and beta are [2*D] (Q then K), the steps are s_y[0], s_y[1]; V keeps the plain quantizer.
+    // Needs dh == 64.  Null: plain quantizers on all three.
+    const float *hn_gamma, *hn_beta; float hn_eps;
 };
 
 // wb / ab: storage bits of the weight / activation operand.  Supported: (4,4) (2,4) (8,8).

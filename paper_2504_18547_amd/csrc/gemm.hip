@@ -19,6 +19,7 @@
 // whose cheap value lies within that bound of a rounding boundary is recomputed with the exact
 // operation sequence.  The result is therefore always the definition's, bit for bit.
 #include "gemm.h"
+#include <type_traits>
 #include "vitq_dev.h"
 
 namespace vitq {
@@ -35,7 +36,7 @@ namespace {
 #define VITQ_S84 2
 #define VITQ_OCC84 3
 #endif
-enum Epi { kEpiGeneric = 0, kEpiF32 = 1, kEpiQuant = 2, kEpiQuantGelu = 3 };
+enum Epi { kEpiGeneric = 0, kEpiF32 = 1, kEpiQuant = 2, kEpiQuantGelu = 3, kEpiHeadNorm = 4 };
 
 // channel c (0..31 within a 32-block) -> MFMA row slot, chosen so that a lane's sixteen
 // accumulator registers (rows 8*(r/4) + 4*(lane/32) + r%4) are channels 16*(lane/32) + r
@@ -167,23 +168,33 @@ __device__ __forceinline__ void epilogue_generic(const GemmParams &p, const v16i
 // register r of the wave is 32 consecutive channels (one full 128-byte line) of tokens
 // m0 + 8*(r/4) + r%4 (+4 for the upper half-wave).  Every store instruction therefore writes
 // two complete lines instead of 64 scattered 16-byte pieces.
-// scs = sc * 2^-shift exactly, so fma((float)acc_scaled, scs, b) == fma((float)acc, sc, b).
+// The caller passes the folded scale (sc * 2^-shift exactly, so fma((float)acc_scaled, scs, b) ==
+// fma((float)acc, sc, b)) with shift 0, or, when the fold was inexact, the plain one and the shift.
+template <bool FULL, bool RES>   // FULL: the whole tile lies inside the matrix (no per-element tests); RES: residual given
 __device__ __forceinline__ void epilogue_f32(const GemmParams &p, const v16i &acc, int shift, int m0, int ch,
-                                             float scs, float bs, bool fold_ok) {
-    if (ch >= p.Nout) return;
-    float sc = scs;
-    if (!fold_ok) sc = p.s_x * p.s_w[p.s_w_per_channel ? ch : 0];   // subnormal-small scales: unfolded
+                                             float sc, float bs, const float (&rv)[16]) {
+    if (!FULL && ch >= p.Nout) return;
     float *out = p.y_out + (int64_t)m0 * p.Nout + ch;
-    const float *res = p.res ? p.res + (int64_t)m0 * p.Nout + ch : nullptr;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int dm = 8 * (r >> 2) + (r & 3);
-        if (m0 + dm < p.M) {
-            const int a = fold_ok ? acc[r] : (acc[r] >> shift);
-            float y = fmaf((float)a, sc, bs);
-            if (res) y = y + res[(int64_t)dm * p.Nout];     // residual stream (each element is read
-            out[(int64_t)dm * p.Nout] = y;                  // by the lane that then writes it)
+        if (FULL || m0 + dm < p.M) {
+            float y = fmaf((float)(acc[r] >> shift), sc, bs);
+            if constexpr (RES) y = y + rv[r];               // residual stream
+            out[(int64_t)dm * p.Nout] = y;
         }
+    }
+}
+// The residual elements of one 32x32 block, in the register order of epilogue_f32 (each element
+// is read by the lane that later writes it, so the stream may be updated in place).
+template <bool FULL>
+__device__ __forceinline__ void load_residual(const GemmParams &p, int m0, int ch, float (&rv)[16]) {
+    if (!FULL && ch >= p.Nout) return;
+    const float *res = p.res + (int64_t)m0 * p.Nout + ch;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int dm = 8 * (r >> 2) + (r & 3);
+        if (FULL || m0 + dm < p.M) rv[r] = res[(int64_t)dm * p.Nout];
     }
 }
 
@@ -281,6 +292,112 @@ __device__ __forceinline__ void epilogue_quant(const GemmParams &p, const v16i &
     }
 }
 
+// ---- per-head LayerNorm quantizers of Q and K in the QKV epilogue (Sec. IV-C, Table I) ----------
+// Heads are 64 channels and a wave's tile is 64 channels x 64 tokens, so a wave holds whole
+// (token, head) groups: after the accumulation, lanes l and l+32 own the two 16-channel halves
+// of each 32-channel block of token l (first token block) and of token 32+l (second block).
+// One v_permlane32_swap per register pair trades those halves, after which lane (l, g) owns all
+// 64 channels of ONE token (block g) and can walk them in order, as Eq. 5 requires: the mean and
+// the sum of squared deviations are the fp32 recurrences in element order, and every level is
+// decided by the sigma-free comparator (a guess from the hardware reciprocal square root only
+// picks which two comparisons are evaluated).  The fp32 linear output never leaves registers.
+// gamma / beta / the folded scales are wave-uniform: they come through scalar loads and LDS
+// broadcasts.
+template <int SB>
+__device__ __forceinline__ void epilogue_headnorm(const GemmParams &p, v16i (&acc)[2][2], int shift, uint8_t *dst,
+                                                  const float *scs64, const float *bs64, float step,
+                                                  const float *gp, const float *bp) {
+    // trade halves: afterwards sw[0] is channel 32*ci + r and sw[1] channel 32*ci + 16 + r of this
+    // lane's token.  The definition's y = fma((float)acc, s_x*s_w[c], b[c]); the caller passes
+    // either the folded scales (which carry 2^-shift exactly) with shift 0, or the plain ones.
+    float v[64];
+    auto to_y = [&](int a, int i) { return fmaf((float)(a >> shift), scs64[i], bs64[i]); };
+#pragma unroll
+    for (int ci = 0; ci < 2; ++ci) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const auto sw = __builtin_amdgcn_permlane32_swap(acc[ci][0][r], acc[ci][1][r], false, false);
+            v[32 * ci + r] = to_y((int)sw[0], 32 * ci + r);
+            v[32 * ci + 16 + r] = to_y((int)sw[1], 32 * ci + 16 + r);
+        }
+        __builtin_amdgcn_sched_barrier(0);   // the two accumulator tiles are dead before the next pair is touched
+    }
+    float mu = 0.0f, m2 = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 64; ++i) {
+        const float d1 = v[i] - mu;
+        mu = mu + d1 / (float)(i + 1);
+        const float d2 = v[i] - mu;
+        const float pr = d1 * d2;
+        m2 = m2 + pr;
+    }
+    const float nf = 64.0f;
+    const float ne = nf * p.hn_eps;
+    const float V = m2 + ne;
+    const float rs = __builtin_amdgcn_rsqf(V / nf);          // for the guess only
+    const float rstep = __builtin_amdgcn_rcpf(step);         // for the guess only
+    const float qminf = p.qminf, qmaxf = p.qmaxf;
+    const int span = (int)(qmaxf - qminf);
+    const float bias8 = -qminf;
+#pragma unroll
+    for (int i = 0; i < 64; ++i) {
+        const float gm = gp[i], bt = bp[i];
+        const float a = v[i] - mu;
+        const float g = a * gm;
+        const float gs = g * fabsf(g);
+        const float L = gs * nf;
+        auto above = [&](float k) {
+            const float rk = (k - 0.5f) * step;
+            const float cc = rk - bt;
+            const float cs = cc * fabsf(cc);
+            const float R = cs * V;
+            return L > R;
+        };
+        const float tt = rintf(fmaf(g, rs, bt) * rstep);
+        float c = (tt == tt) ? __builtin_amdgcn_fmed3f(tt, qminf, qmaxf) : qminf;
+        for (int it = 0; it <= span; ++it) {
+            const bool low_ok = (c <= qminf) || above(c);
+            const bool high_ok = (c >= qmaxf) || !above(c + 1.0f);
+            if (low_ok && high_ok) break;
+            c = c + (!low_ok ? -1.0f : 1.0f);
+        }
+        v[i] = c + bias8;                                  // stored biased: 0 .. qmax - qmin
+        if ((i & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+    }
+    if (!dst) return;
+    if constexpr (SB == 4) {
+        const u32 fix = 0x11111111u * ((u32)bias8 & 0xFu);
+        u32 w[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            u32 ev = 0, od = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                ev = __builtin_amdgcn_cvt_pk_u8_f32(v[8 * j + 2 * i], i, ev);
+                od = __builtin_amdgcn_cvt_pk_u8_f32(v[8 * j + 2 * i + 1], i, od);
+            }
+            const u32 a0 = ev | (od << 4);
+            w[j] = ((a0 | 0x88888888u) - (fix & 0x77777777u)) ^ ((a0 ^ ~fix) & 0x88888888u);
+        }
+        *reinterpret_cast<uint4 *>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
+        *reinterpret_cast<uint4 *>(dst + 16) = make_uint4(w[4], w[5], w[6], w[7]);
+    } else {
+        const u32 fix = 0x01010101u * ((u32)bias8 & 0xFFu);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            u32 w[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                u32 x = 0;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) x = __builtin_amdgcn_cvt_pk_u8_f32(v[16 * q + 4 * j + i], i, x);
+                w[j] = ((x | 0x80808080u) - (fix & 0x7F7F7F7Fu)) ^ ((x ^ ~fix) & 0x80808080u);
+            }
+            *reinterpret_cast<uint4 *>(dst + 16 * q) = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+    }
+}
+
 // ---- direct global -> LDS loads ----------------------------------------------------------------
 // global_load_lds_dwordx4: lane i of the wave writes its 16 bytes to LDS address M0 + 16*i; no
 // VGPRs are used for the data, so several k-stages can be in flight at once.  The compiler does
@@ -345,6 +462,7 @@ void gemm_kernel(GemmParams p) {
     float *s_scs = reinterpret_cast<float *>(smem + S * STAGE);           // [TC] folded scales
     float *s_bs = s_scs + TC;                                             // [TC] biases
     int *s_fold_bad = reinterpret_cast<int *>(s_bs + TC);                 // [1] flag
+    [[maybe_unused]] float *s_raw = s_bs + TC + 4;                        // [TC] plain scales (fp32, head-norm epilogues)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -444,6 +562,7 @@ void gemm_kernel(GemmParams p) {
             const float sc = p.s_x * sw;
             const float folded = ldexpf(sc, -Shift<WB, AB>::value);
             s_scs[c] = folded;
+            if constexpr (EPI == kEpiHeadNorm || EPI == kEpiF32) s_raw[c] = sc;
             s_bs[c] = (ok && p.bias) ? p.bias[ch] : 0.0f;
             if (!(ldexpf(folded, Shift<WB, AB>::value) == sc)) s_fold_bad[0] = 1;
         }
@@ -561,19 +680,64 @@ void gemm_kernel(GemmParams p) {
     constexpr int shift = Shift<WB, AB>::value;
     const bool fold_ok = (EPI != kEpiGeneric) && (s_fold_bad[0] == 0);
     if constexpr (SWAP) {
-        static_for<NC>([&](auto CI) {
-            constexpr int ci = decltype(CI)::value;
-            const int cl = wave_c * WC + ci * 32 + li;     // this lane's channel inside the tile
-            const float scs = s_scs[cl], bs = s_bs[cl];
-            static_for<NTK>([&](auto TI) {
-                constexpr int ti = decltype(TI)::value;
-                const int m0 = t0 + wave_t * WT + ti * 32 + 4 * g;
-                epilogue_f32(p, acc[ci][ti], shift, m0, c0 + cl, scs, bs, fold_ok);
+        // Blocks in turn; the residual of the next block is requested before the current block is
+        // stored, so its loads never queue behind those stores.
+        auto block_pos = [&](int b, int &m0, int &cl) {
+            const int ci = b / NTK, ti = b % NTK;
+            cl = wave_c * WC + ci * 32 + li;               // this lane's channel inside the tile
+            m0 = t0 + wave_t * WT + ti * 32 + 4 * g;
+        };
+        auto run = [&](auto FULLT, auto REST) {
+            constexpr bool FULL = decltype(FULLT)::value, RES = decltype(REST)::value;
+            float rbuf[2][16];                 // residual of the current / the next block
+#pragma unroll
+            for (int r = 0; r < 16; ++r) rbuf[0][r] = rbuf[1][r] = 0.0f;
+            if constexpr (RES) {
+                int m0, cl;
+                block_pos(0, m0, cl);
+                load_residual<FULL>(p, m0, c0 + cl, rbuf[0]);
+            }
+            static_for<NC * NTK>([&](auto BI) {
+                constexpr int b = decltype(BI)::value;
+                int m0, cl;
+                if constexpr (RES && b + 1 < NC * NTK) {
+                    block_pos(b + 1, m0, cl);
+                    load_residual<FULL>(p, m0, c0 + cl, rbuf[(b + 1) & 1]);
+                }
+                block_pos(b, m0, cl);
+                epilogue_f32<FULL, RES>(p, acc[b / NTK][b % NTK], fold_ok ? 0 : shift, m0, c0 + cl,
+                                        fold_ok ? s_scs[cl] : s_raw[cl], s_bs[cl], rbuf[b & 1]);
             });
-        });
+        };
+        // tiles wholly inside the matrix (all but the last row / column of tiles) skip the bounds tests
+        const bool full = t0 + TT <= p.M && c0 + TC <= p.Nout;
+        if (p.res) { if (full) run(std::true_type{}, std::true_type{}); else run(std::false_type{}, std::true_type{}); }
+        else { if (full) run(std::true_type{}, std::false_type{}); else run(std::false_type{}, std::false_type{}); }
     } else {
+        if constexpr (EPI == kEpiHeadNorm) {
+            // Q and K tiles: per-head LayerNorm quantizer; V tiles fall through to the plain one
+            const int cbw = c0 + wave_c * WC;                       // the wave's head starts here
+            if (cbw < 2 * p.D) {
+                static_assert(EPI != kEpiHeadNorm || (NC == 2 && NTK == 2 && WC == 64), "one head per wave");
+                int which;
+                const int64_t ch_part = packed_channel_part(p, cbw, which);
+                const int64_t tk = packed_token_part(p, t0 + wave_t * WT + 32 * g + li);
+                uint8_t *dst = (ch_part >= 0 && tk >= 0) ? p.yq + tk + ch_part : nullptr;
+                const float step = which == 0 ? p.s_y[0] : p.s_y[1];
+                // folded scales unless folding was inexact somewhere in the tile: then the plain
+                // ones (kept behind the flag word) and the explicit shift
+                const float *sc64 = (fold_ok ? s_scs : s_raw) + wave_c * WC;
+                const int sh = fold_ok ? 0 : shift;
+                if (p.yq_sb == 4)
+                    epilogue_headnorm<4>(p, acc, sh, dst, sc64, s_bs + wave_c * WC, step, p.hn_gamma + cbw, p.hn_beta + cbw);
+                else
+                    epilogue_headnorm<8>(p, acc, sh, dst, sc64, s_bs + wave_c * WC, step, p.hn_gamma + cbw, p.hn_beta + cbw);
+                return;
+            }
+        }
+        constexpr bool QUANT = (EPI == kEpiQuant || EPI == kEpiQuantGelu || EPI == kEpiHeadNorm);
         int64_t tok_part[NTK];
-        if constexpr (EPI == kEpiQuant || EPI == kEpiQuantGelu) {
+        if constexpr (QUANT) {
 #pragma unroll
             for (int ti = 0; ti < NTK; ++ti)
                 tok_part[ti] = packed_token_part(p, t0 + wave_t * WT + ti * 32 + li);
@@ -602,7 +766,7 @@ void gemm_kernel(GemmParams p) {
             }
             static_for<NTK>([&](auto TI) {
                 constexpr int ti = decltype(TI)::value;
-                if constexpr (EPI == kEpiQuant || EPI == kEpiQuantGelu) {
+                if constexpr (QUANT) {
                     uint8_t *dst = (ch_part >= 0 && tok_part[ti] >= 0) ? p.yq + tok_part[ti] + ch_part : nullptr;
                     epilogue_quant<EPI == kEpiQuantGelu>(p, acc[ci][ti], shift, dst, s_y, r_y, cb, scs, bs, !fold_ok);
                 } else {
@@ -616,7 +780,8 @@ void gemm_kernel(GemmParams p) {
 
 template <int WB, int AB, int TC, int TT, int WAVES_C, int WAVES_T, int BK, int S, int OCC, int EPI>
 hipError_t launch(const GemmParams &p, hipStream_t stream) {
-    constexpr size_t lds = S * ((size_t)TC * (BK * WB / 8) + (size_t)TT * (BK * AB / 8)) + 2 * TC * sizeof(float) + 16;
+    constexpr size_t lds = S * ((size_t)TC * (BK * WB / 8) + (size_t)TT * (BK * AB / 8)) + 2 * TC * sizeof(float) + 16 +
+                           ((EPI == kEpiHeadNorm || EPI == kEpiF32) ? TC * sizeof(float) : 0);
     auto kern = gemm_kernel<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, S, OCC, EPI>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -636,6 +801,7 @@ hipError_t launch_epi(const GemmParams &p, int epi, hipStream_t stream) {
         case kEpiF32: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, S, OCC, kEpiF32>(p, stream);
         case kEpiQuant: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, S, OCC, kEpiQuant>(p, stream);
         case kEpiQuantGelu: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, S, OCC, kEpiQuantGelu>(p, stream);
+        case kEpiHeadNorm: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, S, OCC, kEpiHeadNorm>(p, stream);
         default: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, S, OCC, kEpiGeneric>(p, stream);
     }
 }
@@ -649,6 +815,12 @@ hipError_t gemm_launch(GemmParams p, int wb, int ab, hipStream_t stream) {
     if (!p.acc_out && p.y_out && !p.yq && p.act == 0) epi = kEpiF32;     // any Nout
     if (aligned && !p.acc_out) {
         if (p.yq && !p.y_out && (p.yq_sb == 4 || p.yq_sb == 8)) epi = p.act == 1 ? kEpiQuantGelu : kEpiQuant;
+    }
+    if (p.hn_gamma) {
+        // the fused per-head LayerNorm quantizers need whole 64-channel heads per wave tile
+        if (epi != kEpiQuant || !p.head_major || p.dh != 64 || p.D % 64 != 0 || p.Nout != 3 * p.D || !p.hn_beta)
+            return hipErrorInvalidValue;
+        epi = kEpiHeadNorm;
     }
     // per-lane operand offsets inside a tile are kept in 32 bits (127 rows * stride + 112)
     if (p.x_stride >= (1 << 24) || p.w_stride >= (1 << 24) || p.M < 1 || p.Nout < 1) return hipErrorInvalidValue;
@@ -665,7 +837,10 @@ hipError_t gemm_launch(GemmParams p, int wb, int ab, hipStream_t stream) {
         p.gelu_guard = ldexpf(1.0f, -18);
         // a step so small that 1/s overflows, or so large that it underflows, takes the exact path
         for (int i = 0; i < 3; ++i)
-            if (!(p.r_y[i] > 0x1p-100f && p.r_y[i] < 0x1p100f)) epi = (epi == kEpiF32) ? epi : kEpiGeneric;
+            if (!(p.r_y[i] > 0x1p-100f && p.r_y[i] < 0x1p100f)) {
+                if (epi == kEpiHeadNorm) return hipErrorInvalidValue;
+                epi = (epi == kEpiF32) ? epi : kEpiGeneric;
+            }
     }
     if (wb == 4 && ab == 4) return launch_epi<4, 4, 128, 128, 2, 2, 128, 3, 3>(p, epi, stream);
     if (wb == 2 && ab == 4) return launch_epi<2, 4, 128, 128, 2, 2, 128, 3, 3>(p, epi, stream);

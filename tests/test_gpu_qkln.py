@@ -45,7 +45,7 @@ def test_qkv_headnorm_op(bits, B, H, N):
     assert np.array_equal(got[2].transpose(0, 2, 1, 3).reshape(M, D), vref)
 
 
-def _block(name, images, bits_w, bits_a, prepack=False):
+def _block(name, images, bits_w, bits_a, prepack=False, steps=None):
     dims = wl.block_dims(name)
     D, H, N, hidden = dims["D"], dims["H"], dims["N"], dims["hidden"]
     B = len(images)
@@ -53,6 +53,8 @@ def _block(name, images, bits_w, bits_a, prepack=False):
     lo, hi = vqo.qrange(bits_a)
     st = dict(wl.block_steps(name, True, bits_w, bits_a))
     st["s_q"] = st["s_k"] = np.float32(3.0 / hi)
+    for k, v in (steps or {}).items():
+        st[k] = np.float32(v)
     wts = quantized_weights(wl.block_weights(name, sharp=True), bits_w)
     wd = device_weights(wts, bits_w, prepack=prepack)
     ln = _ln(D)
@@ -88,6 +90,16 @@ def test_table1_head_shape_n198():
                                                         ("tiny_block", 8, 8, False), ("tiny_attn", 2, 4, False)])
 def test_small_blocks(name, bits_w, bits_a, prepack):
     _block(name, list(range(wl.BLOCKS[name]["batch"])), bits_w, bits_a, prepack)
+
+
+def test_scales_too_small_to_fold():
+    # s_x * s_w * 2^-8 is subnormal: the epilogue must take the unfolded scales and the explicit shift
+    _block("tiny_attn", [0, 1], 4, 4, steps={"s_x": 1e-36})
+
+
+def test_steps_outside_the_fused_epilogue():
+    # 1/s_q beyond 2^100: the QKV linear runs in fp32 and the stand-alone head-norm kernel follows
+    _block("tiny_attn", [0, 1], 4, 4, steps={"s_q": 1e-34})
 
 
 def test_vit_b_block_reduced_batch():
