@@ -20,6 +20,7 @@
  *   quantizer levels/thresholds ........ Sec. IV-B (3-bit reference list), Sec. IV-C
  *   dequantize-first linear ............ Eq. 1 (first line)           [cross-check]
  *   reordered linear ................... Eq. 2
+ *   equivalent bias, absorbed scales ... Eq. 2 (second form), Sec. IV-B
  *   Q.K^T and softmax .................. Eq. 3
  *   shift-based exponential ............ Eq. 4
  *   row-sum-scaled comparator .......... Sec. IV-B, Fig. 4 caption
@@ -295,6 +296,88 @@ int64_t vqo_linear(const int8_t *xq, int64_t M, int64_t K, float s_x,
             if (acc_out) acc_out[m * Nout + c] = acc;
             if (y_out) y_out[m * Nout + c] = y;
             if (yq_out) yq_out[m * Nout + c] = (int8_t)quantize_one(y, s_y, qmin, qmax);
+        }
+    return bad;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Scale absorption for a linear that feeds a quantizer directly (Eq. 2 in its */
+/* second form; Sec. IV-B on absorbing the scales into the quantizer).          */
+/*                                                                            */
+/* Eq. 2 factors the post-scale s_x*s_w[c] out of the sum AND the bias: the     */
+/* bias becomes an "equivalent bias" b[c]/(s_x*s_w[c]) added in the integer     */
+/* domain.  The quantizer that follows is a bank of comparators against the     */
+/* references (k-1/2)*s_y (Sec. IV-B, IV-C); dividing both sides of every       */
+/* comparison by the positive post-scale moves it into the references too, so   */
+/* the whole linear + quantizer is integer:                                     */
+/*     a     = acc + b_int[c]                                                   */
+/*     level = qmin + #{ k in qmin+1..qmax : a > T[c][k] }                      */
+/* Readings (the paper gives the algebra, not the number formats):              */
+/*   - scale_c = s_x*s_w[c] is the fp32 product of Eq. 2's path, then taken as  */
+/*     the real number it is;                                                   */
+/*   - the equivalent bias is rounded to the nearest integer (ties to even),    */
+/*     b_int[c] = rint(b[c]/scale_c) in double precision -- it has to be an     */
+/*     integer to be added to integer accumulators;                             */
+/*   - theta = ((double)k - 0.5)*(double)s_y / scale_c in double precision      */
+/*     (one multiply, one divide), T = floor(theta): for an integer a,          */
+/*     a > theta  <=>  a > floor(theta).  The comparator is strict, so a tie    */
+/*     goes to the lower level.  T is clamped to the int32 range.               */
+/* This mode is NOT bit-identical to vqo_linear's requantized output: that one  */
+/* rounds y to fp32 and adds the bias unrounded; the two differ by at most one  */
+/* level and only near a reference.                                             */
+/* s_y: one step, or one per output channel (s_y_per_channel).                  */
+/* ------------------------------------------------------------------------ */
+int vqo_absorb(float s_x, const float *s_w, int s_w_per_channel, const float *bias,
+               int64_t Nout, const float *s_y, int s_y_per_channel, int bits,
+               int32_t *b_int, int32_t *thr)
+{
+    int qmin = 0, qmax = 0;
+    if (vqo_qrange(bits, 0, &qmin, &qmax)) return -1;
+    const int nthr = qmax - qmin;
+    for (int64_t c = 0; c < Nout; ++c) {
+        const float scale32 = s_x * (s_w_per_channel ? s_w[c] : s_w[0]);
+        const double scale = (double)scale32;
+        const double step = (double)(s_y_per_channel ? s_y[c] : s_y[0]);
+        if (!(scale > 0.0) || !(step > 0.0)) return -1;
+        double bi = bias ? rint((double)bias[c] / scale) : 0.0;
+        if (bi > 2147483647.0) bi = 2147483647.0;
+        if (bi < -2147483648.0) bi = -2147483648.0;
+        b_int[c] = (int32_t)bi;
+        for (int t = 0; t < nthr; ++t) {
+            const int k = qmin + 1 + t;
+            const double theta = ((double)k - 0.5) * step / scale;
+            double T = floor(theta);
+            if (T > 2147483647.0) T = 2147483647.0;
+            if (T < -2147483648.0) T = -2147483648.0;
+            thr[c * nthr + t] = (int32_t)T;
+        }
+    }
+    return 0;
+}
+
+/* The integer-only linear + quantizer.  acc_out and yq_out may be NULL.        */
+/* Returns the number of int32 overflows (of acc, or of acc + b_int).           */
+int64_t vqo_linear_absorbed(const int8_t *xq, int64_t M, int64_t K, const int8_t *wq,
+                            int64_t Nout, const int32_t *b_int, const int32_t *thr, int bits,
+                            int32_t *acc_out, int8_t *yq_out)
+{
+    int qmin = 0, qmax = 0;
+    if (vqo_qrange(bits, 0, &qmin, &qmax)) return -1;
+    const int nthr = qmax - qmin;
+    int64_t bad = 0;
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t c = 0; c < Nout; ++c) {
+            int64_t s = 0;
+            for (int64_t k = 0; k < K; ++k)
+                s += (int64_t)xq[m * K + k] * (int64_t)wq[c * K + k];
+            if (s > INT32_MAX || s < INT32_MIN) ++bad;
+            const int64_t a = s + (b_int ? (int64_t)b_int[c] : 0);
+            if (a > INT32_MAX || a < INT32_MIN) ++bad;
+            int level = qmin;
+            for (int t = 0; t < nthr; ++t)
+                if (a > (int64_t)thr[c * nthr + t]) ++level;
+            if (acc_out) acc_out[m * Nout + c] = (int32_t)s;
+            if (yq_out) yq_out[m * Nout + c] = (int8_t)level;
         }
     return bad;
 }

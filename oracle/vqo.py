@@ -33,7 +33,7 @@ def lib():
         _LIB.vqo_x_gelu_erf.argtypes = [C.c_double]
         _LIB.vqo_shift_exp.restype = C.c_uint32
         _LIB.vqo_shift_exp.argtypes = [C.c_int32, _f32]
-        for name in ("vqo_matmul_nt", "vqo_matmul_nn_u8", "vqo_linear", "vqo_matmul_qk",
+        for name in ("vqo_matmul_nt", "vqo_matmul_nn_u8", "vqo_linear", "vqo_linear_absorbed", "vqo_matmul_qk",
                      "vqo_matmul_pv", "vqo_attention_block"):
             getattr(_LIB, name).restype = _i64
     return _LIB
@@ -175,6 +175,46 @@ def linear(xq, s_x, wq, s_w, bias=None, act=0, s_y=None, bits_y=4, want_acc=True
                            _f32(0.0 if s_y is None else s_y), _int(bits_y), _ptr(yq))
     assert bad >= 0
     return dict(acc=acc, y=y, yq=yq, overflow=bad)
+
+
+def absorb(s_x, s_w, bias, s_y, bits, Nout=None):
+    """Equivalent integer bias and integer thresholds of the absorbed mode.  Returns (b_int [Nout], thr [Nout, 2^bits-1])."""
+    s_w = _c(np.atleast_1d(s_w), np.float32)
+    s_y = _c(np.atleast_1d(s_y), np.float32)
+    if Nout is None:
+        Nout = max(s_w.size, s_y.size, 1 if bias is None else np.size(bias))
+    if bias is not None:
+        bias = _c(bias, np.float32)
+        assert bias.size == Nout
+    assert s_w.size in (1, Nout) and s_y.size in (1, Nout)
+    lo, hi = qrange(bits)
+    b_int = np.empty(Nout, np.int32)
+    thr = np.empty((Nout, hi - lo), np.int32)
+    rc = lib().vqo_absorb(_f32(s_x), _ptr(s_w), _int(int(s_w.size > 1)), _ptr(bias), _i64(Nout), _ptr(s_y),
+                          _int(int(s_y.size > 1)), _int(bits), _ptr(b_int), _ptr(thr))
+    assert rc == 0
+    return b_int, thr
+
+
+def linear_absorbed(xq, wq, b_int, thr, bits, want_acc=True):
+    """Integer-only linear + quantizer.  Returns dict(acc, yq, overflow)."""
+    xq = _c(xq, np.int8)
+    wq = _c(wq, np.int8)
+    M, K = xq.shape
+    Nout, K2 = wq.shape
+    assert K == K2
+    lo, hi = qrange(bits)
+    thr = _c(thr, np.int32)
+    assert thr.shape == (Nout, hi - lo)
+    if b_int is not None:
+        b_int = _c(b_int, np.int32)
+        assert b_int.size == Nout
+    acc = np.empty((M, Nout), np.int32) if want_acc else None
+    yq = np.empty((M, Nout), np.int8)
+    bad = lib().vqo_linear_absorbed(_ptr(xq), _i64(M), _i64(K), _ptr(wq), _i64(Nout), _ptr(b_int), _ptr(thr),
+                                    _int(bits), _ptr(acc), _ptr(yq))
+    assert bad >= 0
+    return dict(acc=acc, yq=yq, overflow=bad)
 
 
 def alpha(s_q, s_k, scale):
