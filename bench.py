@@ -265,6 +265,32 @@ def main():
             "note": "not part of the step; per-head LayerNorm quantizers of Q and K inside the QKV epilogue, "
                     "then the same stages"}
         del ws3
+        # Outside the step: the projection-shaped linear (D -> D) with its requantizer, once through
+        # the floating-point epilogue and once in the integer-only absorbed mode (equivalent bias in
+        # the integer domain, scales absorbed into integer comparator references; Eq. 2, Sec. IV-B).
+        if sa in (4, 8):
+            oq = vitq.QMat.empty(B * N, D, ba)
+            x2 = vitq.QMat.empty(B * N, D, ba)
+            vitq.vq_quantize(tokens, st["s_x"], None, oq)
+            s_next = float(st.get("s_x2", st["s_x"]))
+            b_int, thr = vitq.vq_absorb_thresholds(st["s_o"], wd["sw_proj"].cpu().numpy(), w_fp["b_proj"], [s_next], ba)
+            b_int_d, thr_d = torch.from_numpy(b_int).cuda(), torch.from_numpy(thr).cuda()
+            lin_ms = []
+            for absorbed in (False, True):
+                for i in range(4):
+                    if i == 1:
+                        hip.record(e0, stream)
+                    if absorbed:
+                        vitq.vq_linear_absorbed(oq, wd["w_proj"], b_int_d, thr_d, None, x2)
+                    else:
+                        vitq.vq_linear(oq, st["s_o"], wd["w_proj"], wd["sw_proj"], 1, wd["b_proj"], 0, None, None, s_next, x2)
+                hip.record(e1, stream)
+                torch.cuda.synchronize()
+                lin_ms.append(hip.elapsed_ms(e0, e1) / 3)
+            out["extra"]["vq_linear_absorbed"] = {
+                "ms": lin_ms[1], "ms_vq_linear": lin_ms[0], "shape": [B * N, D, D],
+                "note": "not part of the step; projection-shaped linear + requantizer, integer-only epilogue "
+                        "against the fp32 one"}
         if hidden:
             # Also outside the step: the whole pre-LayerNorm block on the fp32 residual stream
             # (LNQ1 -> attention -> +x -> LNQ2 -> MLP -> +x1), nominal steps for the two LayerNorm

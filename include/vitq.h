@@ -180,6 +180,37 @@ typedef struct vq_block_desc {
 } vq_block_desc;
 
 /*
+ * Absorbed mode: the linear and the quantizer after it as integer arithmetic only (Eq. 2 in its
+ * second form, Sec. IV-B on absorbing the scales into the quantizer).  Eq. 2 moves the bias into
+ * the integer domain as an "equivalent bias" b[c]/(s_x*s_w[c]); the quantizer is a bank of
+ * comparators against (k - 1/2)*s_y, and dividing those references by the positive post-scale
+ * s_x*s_w[c] leaves
+ *     level = qmin + #{ k = qmin+1 .. qmax : acc + b_int[c] > T[c][k] }      (strict: a tie stays below).
+ *
+ * vq_absorb_thresholds -- HOST pointers, plain host arithmetic, no GPU work: fills
+ *   b_int[c]  = rint(bias[c] / scale_c)  (double precision, ties to even; 0 without a bias) and
+ *   thr[c][t] = floor(((qmin+1+t) - 0.5) * s_y / scale_c)  (double: one multiply, one divide),
+ * scale_c = s_x*s_w[c] the fp32 product of Eq. 2 taken as a real number; both clamped to int32.
+ * thr is [out_features][2^bits - 1], non-decreasing along t.  s_w / s_y: one value or one per
+ * channel (flags).  The caller copies both arrays to the device.
+ * Errors: VQ_ERR_NULL, VQ_ERR_BITS (bits outside 2..8), VQ_ERR_STEP (a step or a product of
+ * steps that is not positive and finite).
+ *
+ * vq_linear_absorbed -- DEVICE pointers: yq_out[m][c] = the level above for acc = sum_k xq*wq.
+ * No floating-point value takes part in a decision.  b_int nullable (no bias); thr as above
+ * with 2^(yq_out->bits) - 1 references per channel (the kernel only needs them non-decreasing);
+ * acc_out nullable [rows x out_features] int32.  out_features must be a multiple of 16 and
+ * yq_out use 4- or 8-bit storage (else VQ_ERR_UNSUPPORTED).  Not bit-identical to vq_linear's
+ * requantized output: that one rounds y to fp32 and adds the bias unrounded; the two differ by
+ * at most one level and only next to a reference.
+ */
+vq_status vq_absorb_thresholds(float s_x, const float *s_w, int32_t s_w_per_channel, const float *bias,
+                               int64_t out_features, const float *s_y, int32_t s_y_per_channel, int32_t bits,
+                               int32_t *b_int, int32_t *thr);
+vq_status vq_linear_absorbed(const vq_qmat *xq, const vq_qmat *wq, const int32_t *b_int, const int32_t *thr,
+                             int32_t *acc_out, const vq_qmat *yq_out, void *stream);
+
+/*
  * Offline weight preparation (optional).  The packed format above is the interchange format;
  * the matrix cores consume int8, so a 2-/3-/4-bit weight matrix is expanded either inside every
  * GEMM tile that uses it, or once, here: `out` receives an int8 copy [rows x kp], kp = cols

@@ -205,6 +205,72 @@ vq_status vq_linear(const vq_qmat *xq, float s_x, const vq_qmat *wq, const float
                       nullptr, (hipStream_t)stream);
 }
 
+// ---- absorbed mode: equivalent integer bias, integer comparator references -------------------
+// Host arithmetic in double precision, in the stated order (one multiply, one divide per
+// reference), so that any IEEE-754 host reproduces the same integers.
+vq_status vq_absorb_thresholds(float s_x, const float *s_w, int32_t s_w_per_channel, const float *bias,
+                               int64_t out_features, const float *s_y, int32_t s_y_per_channel, int32_t bits,
+                               int32_t *b_int, int32_t *thr) {
+    if (!s_w || !s_y || !b_int || !thr) return VQ_ERR_NULL;
+    if (bits < 2 || bits > 8) return VQ_ERR_BITS;
+    if (out_features < 0) return VQ_ERR_SHAPE;
+    if (!good_step(s_x)) return VQ_ERR_STEP;
+    const int qmin = -(1 << (bits - 1)), qmax = (1 << (bits - 1)) - 1;
+    const int nthr = qmax - qmin;
+    const double lo = -2147483648.0, hi = 2147483647.0;
+    for (int64_t c = 0; c < out_features; ++c) {
+        const float sw = s_w[s_w_per_channel ? c : 0], sy = s_y[s_y_per_channel ? c : 0];
+        if (!good_step(sw) || !good_step(sy)) return VQ_ERR_STEP;
+        const float scale32 = s_x * sw;                 // Eq. 2's post-scale, the fp32 product
+        if (!good_step(scale32)) return VQ_ERR_STEP;
+        const double scale = (double)scale32, step = (double)sy;
+        double bi = bias ? std::rint((double)bias[c] / scale) : 0.0;     // nearest integer, ties to even
+        bi = bi > hi ? hi : (bi < lo ? lo : bi);
+        b_int[c] = (int32_t)bi;
+        for (int t = 0; t < nthr; ++t) {
+            const double kk = (double)(qmin + 1 + t) - 0.5;
+            const double prod = kk * step;
+            double T = std::floor(prod / scale);        // a > theta  <=>  a > floor(theta) for integer a
+            T = T > hi ? hi : (T < lo ? lo : T);
+            thr[c * nthr + t] = (int32_t)T;
+        }
+    }
+    return VQ_OK;
+}
+
+vq_status vq_linear_absorbed(const vq_qmat *xq, const vq_qmat *wq, const int32_t *b_int, const int32_t *thr,
+                             int32_t *acc_out, const vq_qmat *yq_out, void *stream) {
+    vq_status st = check_linear_operands(xq, wq);
+    if (st != VQ_OK) return st;
+    if (!thr || !yq_out) return VQ_ERR_NULL;
+    if ((st = check_qmat(yq_out, 0)) != VQ_OK) return st;
+    if (yq_out->rows != xq->rows || yq_out->cols != wq->rows) return VQ_ERR_SHAPE;
+    if (yq_out->storage_bits != 4 && yq_out->storage_bits != 8) return VQ_ERR_UNSUPPORTED;
+    if (wq->rows % 16 != 0) return VQ_ERR_UNSUPPORTED;
+    if (((uintptr_t)thr) % 4 != 0 || ((uintptr_t)b_int) % 4 != 0 || ((uintptr_t)acc_out) % 4 != 0) return VQ_ERR_STRIDE;
+    if (xq->rows == 0 || wq->rows == 0) return VQ_OK;
+    GemmParams p{};
+    p.x = (const uint8_t *)xq->data; p.x_stride = xq->row_stride; p.M = (int)xq->rows;
+    p.w = (const uint8_t *)wq->data; p.w_stride = wq->row_stride; p.Nout = (int)wq->rows;
+    p.K = (int)xq->cols;
+    p.kbytes_x16 = (int)row_bytes16(xq);
+    p.kbytes_w16 = (int)row_bytes16(wq);
+    hipStream_t stream_ = (hipStream_t)stream;
+    if (acc_out) {
+        // the accumulators on request (a parity aid): a separate pass through the plain epilogue
+        GemmParams pa = p;
+        pa.acc_out = acc_out;
+        pa.s_x = 1.0f;
+        pa.vec_ok = (p.Nout % 4 == 0 && ((uintptr_t)acc_out) % 16 == 0) ? 1 : 0;
+        if (gemm_launch(pa, wq->storage_bits, xq->storage_bits, stream_) != hipSuccess) return VQ_ERR_HIP;
+    }
+    p.yq = (uint8_t *)yq_out->data; p.yq_stride = yq_out->row_stride; p.yq_sb = yq_out->storage_bits;
+    p.yq_row_bytes16 = (int)row_bytes16(yq_out);
+    level_range(yq_out->bits, &p.qminf, &p.qmaxf);
+    p.ab_bint = b_int; p.ab_thr = thr; p.ab_nthr = (1 << yq_out->bits) - 1;
+    return gemm_launch(p, wq->storage_bits, xq->storage_bits, stream_) == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
 vq_status vq_layernorm_quantize(const float *x, const float *residual, float *sum_out, int64_t rows,
                                 int64_t cols, int64_t ld, const float *gamma, const float *beta, float eps,
                                 float step, const vq_qmat *out, void *stream) {

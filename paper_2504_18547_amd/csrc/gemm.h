@@ -27,6 +27,11 @@ struct GemmParams {
     // and beta are [2*D] (Q then K), the steps are s_y[0], s_y[1]; V keeps the plain quantizer.
     // Needs dh == 64.  Null: plain quantizers on all three.
     const float *hn_gamma, *hn_beta; float hn_eps;
+    // integer-only epilogue (Eq. 2 with the equivalent bias in the integer domain, scales absorbed
+    // into the comparator references): level = qmin + #{t : acc + ab_bint[c] > ab_thr[c][t]}.
+    // ab_thr [Nout][ab_nthr] non-decreasing per channel, ab_bint [Nout] nullable; s_x, s_w, bias,
+    // s_y are not read.  Null ab_thr: the floating-point epilogues.
+    const int32_t *ab_bint, *ab_thr; int ab_nthr;
 };
 
 // wb / ab: storage bits of the weight / activation operand.  Supported: (4,4) (2,4) (8,8).

@@ -36,7 +36,7 @@ namespace {
 #define VITQ_S84 2
 #define VITQ_OCC84 3
 #endif
-enum Epi { kEpiGeneric = 0, kEpiF32 = 1, kEpiQuant = 2, kEpiQuantGelu = 3, kEpiHeadNorm = 4 };
+enum Epi { kEpiGeneric = 0, kEpiF32 = 1, kEpiQuant = 2, kEpiQuantGelu = 3, kEpiHeadNorm = 4, kEpiAbsorbed = 5, kEpiAbsorbedBig = 6 };   // Big: more than 15 references per channel
 
 // channel c (0..31 within a 32-block) -> MFMA row slot, chosen so that a lane's sixteen
 // accumulator registers (rows 8*(r/4) + 4*(lane/32) + r%4) are channels 16*(lane/32) + r
@@ -111,7 +111,8 @@ __device__ __forceinline__ void epilogue_generic(const GemmParams &p, const v16i
     for (int r = 0; r < 16; ++r) {
         const int c = cb + r;
         const bool ok = c < p.Nout;
-        const float sc = p.s_x * (ok ? p.s_w[p.s_w_per_channel ? c : 0] : 1.0f);
+        // (an accumulators-only call carries no scales)
+        const float sc = p.s_x * ((ok && p.s_w) ? p.s_w[p.s_w_per_channel ? c : 0] : 1.0f);
         const float bsr = (ok && p.bias) ? p.bias[c] : 0.0f;
         a[r] = acc[r] >> shift;
         float v = fmaf((float)a[r], sc, bsr);
@@ -198,6 +199,50 @@ __device__ __forceinline__ void load_residual(const GemmParams &p, int m0, int c
     }
 }
 
+// Packs sixteen levels (floats holding level - qmin, i.e. 0 .. qmax - qmin) into 4- or 8-bit
+// two's-complement fields and stores them: 8 or 16 bytes at dst.
+__device__ __forceinline__ void pack_store16(const GemmParams &p, uint8_t *dst, const float (&lv)[16], float bias8) {
+    if (p.yq_sb == 4) {
+        // even-indexed levels in the low nibbles of one word, odd-indexed shifted into the high
+        u32 ev0 = 0, od0 = 0, ev1 = 0, od1 = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            ev0 = __builtin_amdgcn_cvt_pk_u8_f32(lv[2 * i], i, ev0);
+            od0 = __builtin_amdgcn_cvt_pk_u8_f32(lv[2 * i + 1], i, od0);
+            ev1 = __builtin_amdgcn_cvt_pk_u8_f32(lv[8 + 2 * i], i, ev1);
+            od1 = __builtin_amdgcn_cvt_pk_u8_f32(lv[8 + 2 * i + 1], i, od1);
+        }
+        // stored levels are biased by -qmin = 2^(bits-1); remove it per nibble, modulo 16 and
+        // without borrows across nibbles (for 4-bit levels this is a flip of bit 3)
+        const u32 fix = 0x11111111u * ((u32)bias8 & 0xFu);
+        const u32 a0 = ev0 | (od0 << 4), a1 = ev1 | (od1 << 4);
+        const u32 w0 = ((a0 | 0x88888888u) - (fix & 0x77777777u)) ^ ((a0 ^ ~fix) & 0x88888888u);
+        const u32 w1 = ((a1 | 0x88888888u) - (fix & 0x77777777u)) ^ ((a1 ^ ~fix) & 0x88888888u);
+        *reinterpret_cast<uint2 *>(dst) = make_uint2(w0, w1);
+    } else {
+        // 8-bit storage: the bias -qmin = 2^(bits-1) is removed modulo 256
+        const u32 fix = 0x01010101u * ((u32)bias8 & 0xFFu);
+        u32 w[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            u32 v = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v = __builtin_amdgcn_cvt_pk_u8_f32(lv[4 * j + i], i, v);
+            // per-byte subtraction of the bias: (v - fix) without borrows across bytes
+            w[j] = ((v | 0x80808080u) - (fix & 0x7F7F7F7Fu)) ^ ((v ^ ~fix) & 0x80808080u);
+        }
+        *reinterpret_cast<uint4 *>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
+// A 16-channel group that lies wholly beyond the last output channel but inside the 16-byte
+// padded row: the packed format wants zero bytes there.
+__device__ __forceinline__ void store_zero_group(const GemmParams &p, uint8_t *dst) {
+    if (!dst) return;
+    if (p.yq_sb == 4) *reinterpret_cast<uint2 *>(dst) = make_uint2(0u, 0u);
+    else *reinterpret_cast<uint4 *>(dst) = make_uint4(0u, 0u, 0u, 0u);
+}
+
 // ---- guarded fast requantization (Nout % 16 == 0; 4- or 8-bit storage) ------------------------
 // Cheap value: t8 = fma(y, 1/s, -qmin) ~ y/s - qmin, level+(-qmin) = rint(t8).  With T = y/s:
 //   |t8 + qmin - fl(T)| <= |T| * 2^-23 + ulp(t8)/2  <  eps0 = 2^(bits-22)   whenever |T| <= qmax+2,
@@ -259,37 +304,7 @@ __device__ __forceinline__ void epilogue_quant(const GemmParams &p, const v16i &
             lv[r] = __builtin_amdgcn_fmed3f(te, 0.0f, top);
         }
     }
-    if (p.yq_sb == 4) {
-        // even-indexed levels in the low nibbles of one word, odd-indexed shifted into the high
-        u32 ev0 = 0, od0 = 0, ev1 = 0, od1 = 0;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            ev0 = __builtin_amdgcn_cvt_pk_u8_f32(lv[2 * i], i, ev0);
-            od0 = __builtin_amdgcn_cvt_pk_u8_f32(lv[2 * i + 1], i, od0);
-            ev1 = __builtin_amdgcn_cvt_pk_u8_f32(lv[8 + 2 * i], i, ev1);
-            od1 = __builtin_amdgcn_cvt_pk_u8_f32(lv[8 + 2 * i + 1], i, od1);
-        }
-        // stored levels are biased by -qmin = 2^(bits-1); remove it per nibble, modulo 16 and
-        // without borrows across nibbles (for 4-bit levels this is a flip of bit 3)
-        const u32 fix = 0x11111111u * ((u32)bias8 & 0xFu);
-        const u32 a0 = ev0 | (od0 << 4), a1 = ev1 | (od1 << 4);
-        const u32 w0 = ((a0 | 0x88888888u) - (fix & 0x77777777u)) ^ ((a0 ^ ~fix) & 0x88888888u);
-        const u32 w1 = ((a1 | 0x88888888u) - (fix & 0x77777777u)) ^ ((a1 ^ ~fix) & 0x88888888u);
-        *reinterpret_cast<uint2 *>(dst) = make_uint2(w0, w1);
-    } else {
-        // 8-bit storage: the bias -qmin = 2^(bits-1) is removed modulo 256
-        const u32 fix = 0x01010101u * ((u32)bias8 & 0xFFu);
-        u32 w[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            u32 v = 0;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) v = __builtin_amdgcn_cvt_pk_u8_f32(lv[4 * j + i], i, v);
-            // per-byte subtraction of the bias: (v - fix) without borrows across bytes
-            w[j] = ((v | 0x80808080u) - (fix & 0x7F7F7F7Fu)) ^ ((v ^ ~fix) & 0x80808080u);
-        }
-        *reinterpret_cast<uint4 *>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
-    }
+    pack_store16(p, dst, lv, bias8);
 }
 
 // ---- per-head LayerNorm quantizers of Q and K in the QKV epilogue (Sec. IV-C, Table I) ----------
@@ -398,6 +413,48 @@ __device__ __forceinline__ void epilogue_headnorm(const GemmParams &p, v16i (&ac
     }
 }
 
+// ---- integer-only epilogue: equivalent bias + comparator references with the scales absorbed ----
+// (Eq. 2, second form; Sec. IV-B.)  level = qmin + #{t : acc + b_int[c] > T[c][t]}, T non-decreasing
+// in t, so the count is found by bisection: 4 integer comparisons for up to 15 references, 8 for up
+// to 255, no branch, no floating point.  tbl: the tile's references in LDS, rows of kAbsRow entries
+// (INT32_MAX -- never exceeded -- beyond the last one), or, with more than 15 per channel, the
+// caller's table in global memory.
+constexpr int kAbsRow = 17;
+template <bool TBL_LDS>
+__device__ __forceinline__ void epilogue_absorbed(const GemmParams &p, const v16i &acc, int shift, uint8_t *dst,
+                                                  const int *tbl, int64_t tbl_row, const int *bint) {
+    if (!dst) return;
+    const int nthr = p.ab_nthr;
+    constexpr int TOP = TBL_LDS ? 8 : 128;             // first bisection stride: 2^(steps-1)
+    float lv[16];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int4 b4 = *reinterpret_cast<const int4 *>(bint + 4 * q);
+        const int bq[4] = {b4.x, b4.y, b4.z, b4.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int r = 4 * q + i;
+            const int a = (acc[r] >> shift) + bq[i];
+            int pos = 0;                                // references known to be exceeded
+#pragma unroll
+            for (int step = TOP; step >= 1; step >>= 1) {
+                const int t = pos + step - 1;
+                int ref;
+                if constexpr (TBL_LDS) {
+                    ref = tbl[r * kAbsRow + t];
+                } else {
+                    const int v = tbl[(int64_t)r * tbl_row + min(t, nthr - 1)];
+                    ref = t >= nthr ? INT32_MAX : v;
+                }
+                pos += (a > ref) ? step : 0;
+            }
+            lv[r] = (float)pos;
+        }
+        if constexpr (TBL_LDS) __builtin_amdgcn_sched_barrier(0);
+    }
+    pack_store16(p, dst, lv, -p.qminf);
+}
+
 // ---- direct global -> LDS loads ----------------------------------------------------------------
 // global_load_lds_dwordx4: lane i of the wave writes its 16 bytes to LDS address M0 + 16*i; no
 // VGPRs are used for the data, so several k-stages can be in flight at once.  The compiler does
@@ -457,6 +514,7 @@ void gemm_kernel(GemmParams p) {
     static_assert(WC % 32 == 0 && WT % 32 == 0 && TC % 64 == 0 && BK % 64 == 0, "wave tile");
     constexpr int WBUF = TC * WROW, XBUF = TT * XROW, STAGE = WBUF + XBUF;
     constexpr bool SWAP = (EPI == kEpiF32);   // tokens as the MFMA A operand (see epilogue_f32)
+    constexpr bool ABSORBED = (EPI == kEpiAbsorbed || EPI == kEpiAbsorbedBig);   // integer-only epilogue
 
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     float *s_scs = reinterpret_cast<float *>(smem + S * STAGE);           // [TC] folded scales
@@ -544,6 +602,23 @@ void gemm_kernel(GemmParams p) {
             for (int it = 0; it < X_ITERS; ++it) dma16(x_off[it], xk, dst + WBUF + it * (NT * 16));
         }
     };
+    // Integer-only epilogue: this lane's share of the tile's comparator references is requested
+    // now, ahead of every operand load (loads retire in order, so the hand-counted waits of the
+    // main loop are unaffected), and parked in registers until the pipeline buffers are free.
+    constexpr int ABS_ITERS = (EPI == kEpiAbsorbed) ? (TC * kAbsRow + NT - 1) / NT : 1;
+    [[maybe_unused]] int abs_ref[ABS_ITERS];
+    if constexpr (EPI == kEpiAbsorbed) {
+        const int nthr = p.ab_nthr;
+        {
+#pragma unroll
+            for (int k = 0; k < ABS_ITERS; ++k) {
+                const int i = min(k * NT + tid, TC * kAbsRow - 1);
+                const int c = i / kAbsRow, t = i - kAbsRow * c;          // entry t of channel c
+                const int ch = min(c0 + c, p.Nout - 1);
+                abs_ref[k] = p.ab_thr[(int64_t)ch * nthr + min(t, nthr - 1)];           // (pads: replaced when stored)
+            }
+        }
+    }
 #pragma unroll
     for (int st = 0; st < S - 1; ++st)
         if (st < nk) issue(st);
@@ -552,7 +627,11 @@ void gemm_kernel(GemmParams p) {
     // flight: sc = s_x*s_w[c] (the definition's exact product) with the operand factor 2^shift
     // folded in.  The fold is exact unless the result is subnormal; a flag then sends the whole
     // tile through the exact operation sequence.
-    if constexpr (EPI != kEpiGeneric) {
+    if constexpr (ABSORBED) {
+        // per channel: the equivalent bias
+        for (int c = tid; c < TC; c += NT)
+            reinterpret_cast<int *>(s_raw)[c] = p.ab_bint ? p.ab_bint[min(c0 + c, p.Nout - 1)] : 0;
+    } else if constexpr (EPI != kEpiGeneric) {
         if (tid == 0) s_fold_bad[0] = 0;
         __syncthreads();
         for (int c = tid; c < TC; c += NT) {
@@ -678,7 +757,7 @@ void gemm_kernel(GemmParams p) {
 
     // ---- epilogue -------------------------------------------------------------------------
     constexpr int shift = Shift<WB, AB>::value;
-    const bool fold_ok = (EPI != kEpiGeneric) && (s_fold_bad[0] == 0);
+    const bool fold_ok = (EPI != kEpiGeneric && !ABSORBED) && (s_fold_bad[0] == 0);
     if constexpr (SWAP) {
         // Blocks in turn; the residual of the next block is requested before the current block is
         // stored, so its loads never queue behind those stores.
@@ -735,6 +814,46 @@ void gemm_kernel(GemmParams p) {
                 return;
             }
         }
+        if constexpr (ABSORBED) {
+            // The pipeline buffers are free now: with at most 15 references per channel the tile's
+            // table is copied into them (padded rows, see epilogue_absorbed), larger tables are read in place.
+            const int nthr = p.ab_nthr;
+            constexpr bool in_lds = (EPI == kEpiAbsorbed);
+            int *s_tbl = reinterpret_cast<int *>(smem);
+            static_assert(TC * kAbsRow * 4 <= S * STAGE, "reference table exceeds the pipeline buffers");
+            if constexpr (in_lds) {
+#pragma unroll
+                for (int k = 0; k < ABS_ITERS; ++k) {
+                    const int i = k * NT + tid;
+                    const int t = i % kAbsRow;
+                    if (i < TC * kAbsRow) s_tbl[i] = t >= nthr ? INT32_MAX : abs_ref[k];
+                }
+                __syncthreads();
+            }
+            int64_t tok_part[NTK];
+#pragma unroll
+            for (int ti = 0; ti < NTK; ++ti) tok_part[ti] = packed_token_part(p, t0 + wave_t * WT + ti * 32 + li);
+            static_for<NC>([&](auto CI) {
+                constexpr int ci = decltype(CI)::value;
+                const int cl = wave_c * WC + ci * 32 + 16 * g;
+                const int cb = c0 + cl;
+                int which;
+                const int64_t ch_part = packed_channel_part(p, cb, which);
+                const int *bint = reinterpret_cast<const int *>(s_raw) + cl;
+                static_for<NTK>([&](auto TI) {
+                    constexpr int ti = decltype(TI)::value;
+                    uint8_t *dst = (ch_part >= 0 && tok_part[ti] >= 0) ? p.yq + tok_part[ti] + ch_part : nullptr;
+                    if (cb >= p.Nout)
+                        store_zero_group(p, dst);
+                    else if constexpr (in_lds)
+                        epilogue_absorbed<true>(p, acc[ci][ti], shift, dst, s_tbl + cl * kAbsRow, kAbsRow, bint);
+                    else
+                        epilogue_absorbed<false>(p, acc[ci][ti], shift, dst, p.ab_thr + (int64_t)min(cb, p.Nout - 16) * nthr,
+                                                 nthr, bint);
+                });
+            });
+            return;
+        }
         constexpr bool QUANT = (EPI == kEpiQuant || EPI == kEpiQuantGelu || EPI == kEpiHeadNorm);
         int64_t tok_part[NTK];
         if constexpr (QUANT) {
@@ -768,7 +887,8 @@ void gemm_kernel(GemmParams p) {
                 constexpr int ti = decltype(TI)::value;
                 if constexpr (QUANT) {
                     uint8_t *dst = (ch_part >= 0 && tok_part[ti] >= 0) ? p.yq + tok_part[ti] + ch_part : nullptr;
-                    epilogue_quant<EPI == kEpiQuantGelu>(p, acc[ci][ti], shift, dst, s_y, r_y, cb, scs, bs, !fold_ok);
+                    if (cb >= p.Nout) store_zero_group(p, dst);
+                    else epilogue_quant<EPI == kEpiQuantGelu>(p, acc[ci][ti], shift, dst, s_y, r_y, cb, scs, bs, !fold_ok);
                 } else {
                     const int m = t0 + wave_t * WT + ti * 32 + li;
                     epilogue_generic(p, acc[ci][ti], shift, m, cb);
@@ -781,7 +901,7 @@ void gemm_kernel(GemmParams p) {
 template <int WB, int AB, int TC, int TT, int WAVES_C, int WAVES_T, int BK, int S, int OCC, int EPI>
 hipError_t launch(const GemmParams &p, hipStream_t stream) {
     constexpr size_t lds = S * ((size_t)TC * (BK * WB / 8) + (size_t)TT * (BK * AB / 8)) + 2 * TC * sizeof(float) + 16 +
-                           ((EPI == kEpiHeadNorm || EPI == kEpiF32) ? TC * sizeof(float) : 0);
+                           ((EPI == kEpiHeadNorm || EPI == kEpiF32 || EPI == kEpiAbsorbed || EPI == kEpiAbsorbedBig) ? TC * sizeof(float) : 0);
     auto kern = gemm_kernel<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, S, OCC, EPI>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -802,6 +922,8 @@ hipError_t launch_epi(const GemmParams &p, int epi, hipStream_t stream) {
         case kEpiQuant: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, S, OCC, kEpiQuant>(p, stream);
         case kEpiQuantGelu: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, S, OCC, kEpiQuantGelu>(p, stream);
         case kEpiHeadNorm: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, S, OCC, kEpiHeadNorm>(p, stream);
+        case kEpiAbsorbed: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, S, OCC, kEpiAbsorbed>(p, stream);
+        case kEpiAbsorbedBig: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, S, OCC, kEpiAbsorbedBig>(p, stream);
         default: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, S, OCC, kEpiGeneric>(p, stream);
     }
 }
@@ -815,6 +937,13 @@ hipError_t gemm_launch(GemmParams p, int wb, int ab, hipStream_t stream) {
     if (!p.acc_out && p.y_out && !p.yq && p.act == 0) epi = kEpiF32;     // any Nout
     if (aligned && !p.acc_out) {
         if (p.yq && !p.y_out && (p.yq_sb == 4 || p.yq_sb == 8)) epi = p.act == 1 ? kEpiQuantGelu : kEpiQuant;
+    }
+    if (p.ab_thr) {
+        // integer-only epilogue: packed output only, whole 16-channel groups, 4- or 8-bit storage
+        if (!aligned || p.acc_out || p.y_out || !p.yq || (p.yq_sb != 4 && p.yq_sb != 8) || p.act != 0 ||
+            p.ab_nthr < 1 || p.ab_nthr > 255 || p.hn_gamma)
+            return hipErrorInvalidValue;
+        epi = p.ab_nthr <= 15 ? kEpiAbsorbed : kEpiAbsorbedBig;
     }
     if (p.hn_gamma) {
         // the fused per-head LayerNorm quantizers need whole 64-channel heads per wave tile
@@ -831,7 +960,7 @@ hipError_t gemm_launch(GemmParams p, int wb, int ab, hipStream_t stream) {
             if ((1 << sft) == p.dh) p.dh_shift = sft;
         if (p.M >= (1 << 22)) return hipErrorInvalidValue;
     }
-    if (p.yq) {
+    if (p.yq && epi != kEpiAbsorbed && epi != kEpiAbsorbedBig) {
         for (int i = 0; i < 3; ++i) p.r_y[i] = 1.0f / p.s_y[i];
         p.eps0 = ldexpf(1.0f, (p.qmaxf > 7.5f ? 8 : 4) - 22);
         p.gelu_guard = ldexpf(1.0f, -18);

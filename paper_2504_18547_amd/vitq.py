@@ -18,7 +18,8 @@ STATUS_NAMES = ["VQ_OK", "VQ_ERR_NULL", "VQ_ERR_SHAPE", "VQ_ERR_BITS", "VQ_ERR_S
 EXPORTS = ["vq_status_string", "vq_weight_steps", "vq_quantize", "vq_linear", "vq_matmul_qk",
            "vq_matmul_pv", "vq_attention_block_workspace", "vq_attention_block",
            "vq_prepack_weight_bytes", "vq_prepack_weight", "vq_linear_prepacked", "vq_layernorm_quantize",
-           "vq_vit_block_workspace", "vq_vit_block", "vq_qkv_headnorm"]
+           "vq_vit_block_workspace", "vq_vit_block", "vq_qkv_headnorm", "vq_absorb_thresholds",
+           "vq_linear_absorbed"]
 
 
 class VitqError(RuntimeError):
@@ -87,6 +88,8 @@ def lib():
         _lib.vq_prepack_weight.argtypes = [qp, vp, C.c_size_t, vp]
         _lib.vq_linear_prepacked.argtypes = [qp, C.c_float, qp, vp, vp, C.c_int32, vp, C.c_int32, vp, vp,
                                              C.c_float, qp, vp]
+        _lib.vq_absorb_thresholds.argtypes = [C.c_float, vp, C.c_int32, vp, C.c_int64, vp, C.c_int32, C.c_int32, vp, vp]
+        _lib.vq_linear_absorbed.argtypes = [qp, qp, vp, vp, vp, qp, vp]
         _lib.vq_layernorm_quantize.argtypes = [vp, vp, vp, C.c_int64, C.c_int64, C.c_int64, vp, vp, C.c_float,
                                                C.c_float, qp, vp]
         _lib.vq_qkv_headnorm.argtypes = [vp, C.c_int64, C.c_int32, C.c_int32, C.c_int32, vp, vp, C.c_float,
@@ -201,6 +204,33 @@ def vq_linear_prepacked(xq, s_x, wq, wp, s_w, s_w_per_channel, bias, act, acc_ou
     _check(lib().vq_linear_prepacked(_q(xq), float(s_x), _q(wq), _ptr(wp), _ptr(s_w), int(s_w_per_channel),
                                      _ptr(bias), int(act), _ptr(acc_out), _ptr(y_out), float(s_y), _q(yq_out),
                                      _stream()), "vq_linear_prepacked")
+
+
+def vq_absorb_thresholds(s_x, s_w, bias, s_y, bits):
+    """Host arrays in, host arrays out: s_w, s_y float32 numpy arrays of one value or one per channel
+    (their larger size, or the bias', is the channel count); returns (b_int [Nout], thr [Nout, 2^bits-1]) int32."""
+    import numpy as np
+    s_w = np.ascontiguousarray(np.atleast_1d(s_w), np.float32)
+    s_y = np.ascontiguousarray(np.atleast_1d(s_y), np.float32)
+    n = max(s_w.size, s_y.size, 1 if bias is None else int(np.size(bias)))
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, np.float32)
+        if bias.size != n:
+            raise ValueError("bias must hold one value per output channel")
+    if s_w.size not in (1, n) or s_y.size not in (1, n):
+        raise ValueError("steps must hold one value or one per output channel")
+    nthr = (1 << int(bits)) - 1 if 2 <= int(bits) <= 8 else 1
+    b_int = np.zeros(n, np.int32)
+    thr = np.zeros((n, nthr), np.int32)
+    hp = lambda a: None if a is None else a.ctypes.data_as(C.c_void_p)
+    _check(lib().vq_absorb_thresholds(float(s_x), hp(s_w), int(s_w.size > 1), hp(bias), n, hp(s_y), int(s_y.size > 1),
+                                      int(bits), hp(b_int), hp(thr)), "vq_absorb_thresholds")
+    return b_int, thr
+
+
+def vq_linear_absorbed(xq, wq, b_int, thr, acc_out, yq_out):
+    _check(lib().vq_linear_absorbed(_q(xq), _q(wq), _ptr(b_int), _ptr(thr), _ptr(acc_out), _q(yq_out), _stream()),
+           "vq_linear_absorbed")
 
 
 def vq_matmul_qk(q, k, B, H, N, s_q, s_k, scale, s_acc_out, p_out):

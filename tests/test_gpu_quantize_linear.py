@@ -190,3 +190,18 @@ def test_failed_check_leaves_outputs_untouched():
     assert e.value.status == vitq.STATUS_NAMES.index("VQ_ERR_STEP")
     torch.cuda.synchronize()
     assert torch.all(y == 3.0)
+
+
+@pytest.mark.parametrize("bits,Nout", [(4, 48), (8, 16), (3, 80)])
+def test_requantized_only_output_keeps_the_row_padding_zero(bits, Nout):
+    # only yq requested: the specialised epilogue runs; the bytes between the last channel and the
+    # 16-byte padded row end must come out zero (the next linear reads them as operand values)
+    rng = np.random.default_rng(bits + Nout)
+    xq, wq, s_w, bias = _rand_case(rng, 70, 128, Nout, bits, bits)
+    xd, wd = to_qmat(xq, bits), to_qmat(wq, bits)
+    yq = vitq.QMat.empty(70, Nout, bits)
+    yq.data.fill_(0xEE)
+    vitq.vq_linear(xd, np.float32(0.31), wd, dev(s_w), 1, dev(bias), 0, None, None, np.float32(0.05), yq)
+    torch.cuda.synchronize()
+    ref = vqo.linear(xq, np.float32(0.31), wq, s_w, bias=bias, s_y=np.float32(0.05), bits_y=bits)
+    assert np.array_equal(yq.data.cpu().numpy(), vqo.pack(ref["yq"], storage_of(bits)))

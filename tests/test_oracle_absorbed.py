@@ -133,3 +133,20 @@ def test_per_channel_output_steps_and_saturating_thresholds():
     wq = np.array([[7, 7]] * 3, np.int8)
     r = vqo.linear_absorbed(xq, wq, None, thr, 4)
     assert r["yq"][0, 2] == -8 + 7 + (1 if 98 > thr[2, 7] else 0)
+
+
+def test_library_host_helper_reproduces_the_oracle_integers():
+    # vq_absorb_thresholds is host arithmetic (no GPU): written independently in the library, it
+    # must land on the same integers as the oracle for every bit width
+    from paper_2504_18547_amd import vitq
+    rng = np.random.default_rng(40)
+    for bits in (2, 3, 4, 5, 8):
+        n = 64
+        s_w = rng.uniform(1e-4, 0.05, n).astype(np.float32)
+        bias = rng.normal(0, 0.3, n).astype(np.float32)
+        s_y = rng.uniform(0.01, 0.5, n).astype(np.float32)
+        s_x = np.float32(rng.uniform(0.01, 0.2))
+        for b, sy in ((bias, s_y), (None, s_y[:1])):
+            got = vitq.vq_absorb_thresholds(s_x, s_w, b, sy, bits)
+            want = vqo.absorb(s_x, s_w, b, sy, bits, Nout=n)
+            assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1])
