@@ -16,11 +16,29 @@
 // stepping the guess until both agree; the guess only chooses which comparisons are made, every
 // decision is the comparator's.
 #include "layernorm.h"
+#include <type_traits>
 #include "vitq_dev.h"
 
 namespace vitq {
 
 namespace {
+
+// RN(1/k), k = 1 .. kRkMax, evaluated by the compiler (IEEE division).  With rk = RN(1/k):
+//     q0 = RN(d*rk),  r = d - q0*k (exact in one FMA),  q = RN(q0 + r*rk)
+// equals RN(d/k) for EVERY fp32 significand of d and every k <= 16384 -- checked exhaustively on
+// the CPU (2^23 significands x 16384 divisors, no mismatch) -- and the exponent of d only scales
+// all three steps, as long as q0 stays a normal number and nothing overflows: 2^-100 <= |d| <= 2^120.
+#ifndef VITQ_LN_CH
+#define VITQ_LN_CH 16      // elements a lane requests at a time in phase 1
+#endif
+constexpr int kRkMax = 4096;
+struct RkTable {
+    float v[kRkMax + 1];
+    constexpr RkTable() : v{} {
+        for (int k = 1; k <= kRkMax; ++k) v[k] = 1.0f / (float)k;
+    }
+};
+__device__ const RkTable g_rk{};
 
 constexpr int kLnRows = 64;       // rows per workgroup (one lane each in phase 1)
 constexpr int kLnThreads = 256;   // threads per workgroup: all sixteen waves work in phase 2
@@ -36,54 +54,82 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_quantize_kernel(LnParams
 
     // ---- phase 1: Eq. 5, mu_i = mu_{i-1} + (x_i - mu_{i-1}) / i,
     //                     M_i  = M_{i-1}  + (x_i - mu_{i-1}) * (x_i - mu_i)
-    if (tid < kLnRows && row0 + tid < p.rows) {
-        const float *xr = p.x + (row0 + tid) * p.ld;
-        const float *rr = p.res ? p.res + (row0 + tid) * p.ld : nullptr;
+    // The wave that walks the rows rotates with the workgroup index, so that the workgroups
+    // sharing a CU keep different SIMDs busy with their recurrences.
+    const int p1 = tid - (int)(blockIdx.x % kLnWaves) * 64;        // row of this lane in phase 1, if in [0, 64)
+    if (p1 >= 0 && p1 < kLnRows && row0 + p1 < p.rows) {
+        const float *xr = p.x + (row0 + p1) * p.ld;
+        const float *rr = p.res ? p.res + (row0 + p1) * p.ld : nullptr;
         float mu = 0.0f, m2 = 0.0f;
-        auto step1 = [&](float xi, int i1) {      // i1 = 1-based index of the element
-            const float d1 = xi - mu;
-            mu = mu + d1 / (float)i1;
-            const float d2 = xi - mu;
-            const float pr = d1 * d2;
-            m2 = m2 + pr;
-        };
-        int j = 0;
-        if (VEC) {
-            constexpr int CH = 16;
-            const int full = cols / CH * CH;
-            auto load16 = [&](int j0, float (&v)[CH]) {
-#pragma unroll
-                for (int q = 0; q < CH / 4; ++q) {
-                    float4 a = *reinterpret_cast<const float4 *>(xr + j0 + 4 * q);
-                    if (rr) {
-                        const float4 b = *reinterpret_cast<const float4 *>(rr + j0 + 4 * q);
-                        a.x = a.x + b.x; a.y = a.y + b.y; a.z = a.z + b.z; a.w = a.w + b.w;
-                    }
-                    v[4 * q] = a.x; v[4 * q + 1] = a.y; v[4 * q + 2] = a.z; v[4 * q + 3] = a.w;
+        // One pass over the row.  FAST replaces the IEEE division d1 / i by the two-FMA correction
+        // of d1 * RN(1/i) (see g_rk), which gives the same bits whenever d1 is zero or an ordinary
+        // finite number: the pass tracks the largest and the smallest nonzero |d1| and reports
+        // whether that held; the caller repeats the row with the division otherwise.
+        auto walk = [&](auto FAST_T) -> bool {
+            constexpr bool FAST = decltype(FAST_T)::value;
+            mu = 0.0f; m2 = 0.0f;
+            float hi = 0.0f, lo = 1.0f;
+            auto step1 = [&](float xi, int i1) {      // i1 = 1-based index of the element
+                const float d1 = xi - mu;
+                float q;
+                if constexpr (FAST) {
+                    const float kf = (float)i1, rk = g_rk.v[i1];
+                    const float q0 = d1 * rk;
+                    const float r = fmaf(-q0, kf, d1);
+                    q = fmaf(r, rk, q0);
+                    hi = fmaxf(hi, fabsf(d1));
+                    lo = fminf(lo, d1 == 0.0f ? 1.0f : fabsf(d1));
+                } else {
+                    q = d1 / (float)i1;
                 }
+                mu = mu + q;
+                const float d2 = xi - mu;
+                const float pr = d1 * d2;
+                m2 = m2 + pr;
             };
-            if (full > 0) {
-                float cur[CH], nxt[CH];
-                load16(0, cur);
-                for (; j < full; j += CH) {
-                    if (j + CH < full) load16(j + CH, nxt);
+            int j = 0;
+            if (VEC) {
+                constexpr int CH = VITQ_LN_CH;
+                const int full = cols / CH * CH;
+                auto load_chunk = [&](int j0, float (&v)[CH]) {
 #pragma unroll
-                    for (int i = 0; i < CH; ++i) step1(cur[i], j + i + 1);
+                    for (int q = 0; q < CH / 4; ++q) {
+                        float4 a = *reinterpret_cast<const float4 *>(xr + j0 + 4 * q);
+                        if (rr) {
+                            const float4 b = *reinterpret_cast<const float4 *>(rr + j0 + 4 * q);
+                            a.x = a.x + b.x; a.y = a.y + b.y; a.z = a.z + b.z; a.w = a.w + b.w;
+                        }
+                        v[4 * q] = a.x; v[4 * q + 1] = a.y; v[4 * q + 2] = a.z; v[4 * q + 3] = a.w;
+                    }
+                };
+                if (full > 0) {
+                    float cur[CH], nxt[CH];
+                    load_chunk(0, cur);
+                    for (; j < full; j += CH) {
+                        load_chunk(min(j + CH, full - CH), nxt);      // (the last one re-reads its own chunk: no branch)
 #pragma unroll
-                    for (int i = 0; i < CH; ++i) cur[i] = nxt[i];
+                        for (int i = 0; i < CH; ++i) step1(cur[i], j + i + 1);
+#pragma unroll
+                        for (int i = 0; i < CH; ++i) cur[i] = nxt[i];
+                    }
                 }
             }
-        }
-        for (; j < cols; ++j) {                   // ragged tail, unaligned rows
-            float t = xr[j];
-            if (rr) t = t + rr[j];
-            step1(t, j + 1);
-        }
+            for (; j < cols; ++j) {                   // ragged tail, unaligned rows
+                float t = xr[j];
+                if (rr) t = t + rr[j];
+                step1(t, j + 1);
+            }
+            // (a NaN deviation is skipped by the max but makes mu NaN; an infinite one shows in hi)
+            return !FAST || (hi <= 0x1p120f && lo >= 0x1p-100f && mu == mu);
+        };
+        bool done = false;
+        if (cols <= kRkMax) done = walk(std::true_type{});
+        if (!done) walk(std::false_type{});
         const float ne = nf * p.eps;
         const float V = m2 + ne;
-        s_mu[tid] = mu;
-        s_v[tid] = V;
-        s_rs[tid] = __builtin_amdgcn_rsqf(V / nf);      // for the guess only
+        s_mu[p1] = mu;
+        s_v[p1] = V;
+        s_rs[p1] = __builtin_amdgcn_rsqf(V / nf);      // for the guess only
     }
     __syncthreads();
 

@@ -78,6 +78,14 @@ def test_gamma_of_any_sign_constant_rows_and_extreme_values():
     x[6, :] *= 1e-20                          # squares underflow
     x[8, 17] = np.inf
     x[9, 0] = np.nan                          # every comparison false from there on
+    # deviations outside the range in which the kernel replaces the division of Eq. 5 by a corrected
+    # reciprocal multiply (it must notice and divide), and one row that mixes both regimes
+    x[10, :] *= 1e37
+    x[11, :] *= 1e-33
+    x[12, :] *= 1e-41                         # subnormal inputs
+    x[13, 40:] *= 1e-36
+    x[14, :] = 3.0e-38
+    x[14, 100] = 3.0000004e-38                # a subnormal deviation from an ordinary mean
     for eps in (0.0, 1e-5):
         _check(x, gamma, beta, eps, np.float32(0.3), 4)
     _check(x, gamma, beta, 1e-5, np.float32(0.02), 8)
