@@ -316,7 +316,7 @@ __device__ __forceinline__ void epilogue_quant(const GemmParams &p, const v16i &
 // the sum of squared deviations are the fp32 recurrences in element order, and every level is
 // decided by the sigma-free comparator (a guess from the hardware reciprocal square root only
 // picks which two comparisons are evaluated).  The fp32 linear output never leaves registers.
-// gamma / beta / the folded scales are wave-uniform: they come through scalar loads and LDS
+// gamma / beta / the folded scales are wave-uniform: staged in LDS once per tile and read as
 // broadcasts.
 template <int SB>
 __device__ __forceinline__ void epilogue_headnorm(const GemmParams &p, v16i (&acc)[2][2], int shift, uint8_t *dst,
@@ -521,6 +521,7 @@ void gemm_kernel(GemmParams p) {
     float *s_bs = s_scs + TC;                                             // [TC] biases
     int *s_fold_bad = reinterpret_cast<int *>(s_bs + TC);                 // [1] flag
     [[maybe_unused]] float *s_raw = s_bs + TC + 4;                        // [TC] plain scales (fp32, head-norm epilogues)
+    [[maybe_unused]] float *s_hg = s_raw + TC, *s_hb = s_raw + 2 * TC;    // [TC] each: gamma, beta of the head-norm epilogue
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -642,6 +643,11 @@ void gemm_kernel(GemmParams p) {
             const float folded = ldexpf(sc, -Shift<WB, AB>::value);
             s_scs[c] = folded;
             if constexpr (EPI == kEpiHeadNorm || EPI == kEpiF32) s_raw[c] = sc;
+            if constexpr (EPI == kEpiHeadNorm) {
+                const bool qk = ch < 2 * p.D;          // V channels have no LayerNorm
+                s_hg[c] = qk ? p.hn_gamma[ch] : 0.0f;
+                s_hb[c] = qk ? p.hn_beta[ch] : 0.0f;
+            }
             s_bs[c] = (ok && p.bias) ? p.bias[ch] : 0.0f;
             if (!(ldexpf(folded, Shift<WB, AB>::value) == sc)) s_fold_bad[0] = 1;
         }
@@ -808,9 +814,9 @@ void gemm_kernel(GemmParams p) {
                 const float *sc64 = (fold_ok ? s_scs : s_raw) + wave_c * WC;
                 const int sh = fold_ok ? 0 : shift;
                 if (p.yq_sb == 4)
-                    epilogue_headnorm<4>(p, acc, sh, dst, sc64, s_bs + wave_c * WC, step, p.hn_gamma + cbw, p.hn_beta + cbw);
+                    epilogue_headnorm<4>(p, acc, sh, dst, sc64, s_bs + wave_c * WC, step, s_hg + wave_c * WC, s_hb + wave_c * WC);
                 else
-                    epilogue_headnorm<8>(p, acc, sh, dst, sc64, s_bs + wave_c * WC, step, p.hn_gamma + cbw, p.hn_beta + cbw);
+                    epilogue_headnorm<8>(p, acc, sh, dst, sc64, s_bs + wave_c * WC, step, s_hg + wave_c * WC, s_hb + wave_c * WC);
                 return;
             }
         }
@@ -901,7 +907,8 @@ void gemm_kernel(GemmParams p) {
 template <int WB, int AB, int TC, int TT, int WAVES_C, int WAVES_T, int BK, int S, int OCC, int EPI>
 hipError_t launch(const GemmParams &p, hipStream_t stream) {
     constexpr size_t lds = S * ((size_t)TC * (BK * WB / 8) + (size_t)TT * (BK * AB / 8)) + 2 * TC * sizeof(float) + 16 +
-                           ((EPI == kEpiHeadNorm || EPI == kEpiF32 || EPI == kEpiAbsorbed || EPI == kEpiAbsorbedBig) ? TC * sizeof(float) : 0);
+                           ((EPI == kEpiHeadNorm || EPI == kEpiF32 || EPI == kEpiAbsorbed || EPI == kEpiAbsorbedBig) ? TC * sizeof(float) : 0) +
+                           (EPI == kEpiHeadNorm ? 2 * TC * sizeof(float) : 0);
     auto kern = gemm_kernel<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, S, OCC, EPI>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
