@@ -59,7 +59,8 @@ def cpu_baseline(name, sharp, bits_w, bits_a, ops_per_image):
     from paper_2504_18547_amd import workloads as wl
     threads = min(vqo.num_threads(), 16)
     dims = wl.block_dims(name)
-    n_img = 12 * threads
+    # sized for roughly 10-15 s of CPU work: 24 ViT-B blocks per thread, fewer of a larger block
+    n_img = threads * int(min(64, max(2, round(24 * 2.9e9 / ops_per_image))))
     st = wl.block_steps(name, sharp, bits_w, bits_a)
     w_fp = wl.block_weights(name, sharp=sharp)
     wts = {}
