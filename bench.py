@@ -101,8 +101,8 @@ def main():
                          "traffic, used to scale the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (every image is independent; see DESIGN.md "
-              "for how the path would shard); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        print("bench.py: this build runs on exactly one GPU (images are independent, so the path would shard by "
+              "image with no communication); --gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
