@@ -21,6 +21,9 @@
 #ifndef VITQ_ATT_OCC
 #define VITQ_ATT_OCC 4      // workgroups per CU aimed at by the 4-bit kernels of up to 13 key tiles
 #endif
+#ifndef VITQ_ATT_OCC8
+#define VITQ_ATT_OCC8 4     // the same for 8-bit operands or 8-bit P (143 -> 135 us on the W8A8 ViT-B block)
+#endif
 #ifndef VITQ_ATT_GROUP
 #define VITQ_ATT_GROUP 2    // key tiles between scheduling fences (bounds the loads in flight, hence registers)
 #endif
@@ -54,7 +57,7 @@ __device__ __forceinline__ u32 shift_exp_fixed(int d, float alpha) {
 
 // TAIL: N > 16*(NT-1), i.e. every key tile but the last holds only real keys (no masking there).
 template <int NT, int SB, int MODE, bool P8, bool LUT, bool TAIL>
-__global__ __launch_bounds__(256, (NT <= 13 ? ((SB == 4 && !P8) ? VITQ_ATT_OCC : 2) : 1)) void attention_kernel(AttnParams p) {
+__global__ __launch_bounds__(256, (NT <= 13 ? ((SB == 4 && !P8) ? VITQ_ATT_OCC : VITQ_ATT_OCC8) : 1)) void attention_kernel(AttnParams p) {
     constexpr int NCH = (NT + 3) / 4;                 // 64-key chunks of the P.V contraction
     constexpr int NKEYP = NCH * 64;                   // padded key count of V^T rows
     constexpr int KROW = 64 * SB / 8;                 // bytes of one packed K row
