@@ -150,3 +150,19 @@ def test_library_host_helper_reproduces_the_oracle_integers():
             got = vitq.vq_absorb_thresholds(s_x, s_w, b, sy, bits)
             want = vqo.absorb(s_x, s_w, b, sy, bits, Nout=n)
             assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1])
+
+
+def test_library_host_helper_rejects_bad_arguments():
+    import pytest
+    from paper_2504_18547_amd import vitq
+    s_w = np.float32([0.01, 0.02])
+    code = lambda name: vitq.STATUS_NAMES.index(name)
+    for bits in (1, 9):
+        with pytest.raises(vitq.VitqError) as e:
+            vitq.vq_absorb_thresholds(0.1, s_w, None, [0.1], bits)
+        assert e.value.status == code("VQ_ERR_BITS")
+    for s_x, sw, sy in ((0.0, s_w, [0.1]), (0.1, np.float32([0.01, -1.0]), [0.1]), (0.1, s_w, [float("inf")]),
+                        (1e-30, np.float32([1e-30, 1.0]), [0.1])):          # the last: s_x*s_w underflows to zero
+        with pytest.raises(vitq.VitqError) as e:
+            vitq.vq_absorb_thresholds(s_x, sw, None, sy, 4)
+        assert e.value.status == code("VQ_ERR_STEP")
