@@ -315,6 +315,28 @@ def main():
                                             "tops": B * ops_img / (pl_ms * 1e-3) / 1e12,
                                             "note": "not part of the step; fp32 stream in and out, two LayerNorm "
                                                     "quantizers and both residual adds included"}
+        # Outside the step, experimental: the fc2-shaped linear (hidden -> D, fp32 out) with both operands
+        # re-coded as 6-bit E3M2 values on the scaled-MFMA instruction, against the int8 path.
+        if sa == 4 and hidden:
+            hq = vitq.QMat.empty(B * N, hidden, ba)
+            hq.data.copy_(torch.randint(0, 256, hq.data.shape, dtype=torch.uint8, device="cuda"))
+            h6, w6 = vitq.vq_recode_e3m2(hq), vitq.vq_recode_e3m2(wd["w_fc2"])
+            f6_ms = []
+            for f6 in (False, True):
+                for i in range(4):
+                    if i == 1:
+                        hip.record(e0, stream)
+                    if f6:
+                        vitq.vq_linear_e3m2(h6, B * N, w6, D, hidden, st["s_h"], wd["sw_fc2"], 1, wd["b_fc2"], y)
+                    else:
+                        vitq.vq_linear(hq, st["s_h"], wd["w_fc2"], wd["sw_fc2"], 1, wd["b_fc2"], 0, None, y, 0.0, None)
+                hip.record(e1, stream)
+                torch.cuda.synchronize()
+                f6_ms.append(hip.elapsed_ms(e0, e1) / 3)
+            out["extra"]["vq_linear_e3m2"] = {
+                "ms": f6_ms[1], "ms_vq_linear": f6_ms[0], "shape": [B * N, hidden, D],
+                "note": "not part of the step; experimental 6-bit-float operands (same results), uniform random levels"}
+            del hq, h6, w6
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(name, args.sharp, bw, ba, ops_img)
     print(json.dumps(out))

@@ -211,6 +211,30 @@ vq_status vq_linear_absorbed(const vq_qmat *xq, const vq_qmat *wq, const int32_t
                              int32_t *acc_out, const vq_qmat *yq_out, void *stream);
 
 /*
+ * Experimental: the reordered linear (Eq. 2) on the 6-bit-float matrix format.  CDNA4's scaled
+ * MFMA takes E3M2 operands (1 sign, 3 exponent, 2 mantissa bits, bias 3: every integer in
+ * [-8, 8] is a value) at twice the int8 rate with fp32 accumulation; sums of such integer
+ * products stay far below 2^24, where that accumulation is exact, so the result is the same
+ * integer contraction.  Operands must be stored as E3M2 codes in the kernel's operand order:
+ * a row is a sequence of 96-byte stages of 128 values (padded with zero codes to whole
+ * stages); quarter q = 2s + h (s, h in {0,1}) of a stage, values 32q..32q+31, is a 192-bit
+ * string with value j at bits 6j..6j+5; its first 128 bits are the 16-byte piece 3h + s of the
+ * stage and its last 64 bits are half s of piece 3h + 2.  vq_recode_e3m2 makes such a copy of a
+ * packed matrix with 4-bit storage (levels of 2..4 bits).
+ *   vq_recode_e3m2_bytes: size of that copy (rows * ceil(cols/128) * 96).
+ *   vq_recode_e3m2: out device, 16-byte aligned, at least that size (else VQ_ERR_WORKSPACE).
+ *   vq_linear_e3m2: y[m][c] = fma(sum_k x[m][k]*w[c][k], s_x*s_w[c], bias ? bias[c] : 0), fp32
+ *     [rows x out_features]; x6 / w6 are re-coded matrices with `cols` values per row; s_w one
+ *     value or one per channel; the fp32 output equals vq_linear's y_out bit for bit.
+ * storage_bits other than 4: VQ_ERR_UNSUPPORTED.
+ */
+vq_status vq_recode_e3m2_bytes(const vq_qmat *m, size_t *bytes);
+vq_status vq_recode_e3m2(const vq_qmat *m, void *out, size_t out_bytes, void *stream);
+vq_status vq_linear_e3m2(const void *x6, int64_t rows, const void *w6, int64_t out_features, int64_t cols,
+                         float s_x, const float *s_w, int32_t s_w_per_channel, const float *bias, float *y_out,
+                         void *stream);
+
+/*
  * Offline weight preparation (optional).  The packed format above is the interchange format;
  * the matrix cores consume int8, so a 2-/3-/4-bit weight matrix is expanded either inside every
  * GEMM tile that uses it, or once, here: `out` receives an int8 copy [rows x kp], kp = cols

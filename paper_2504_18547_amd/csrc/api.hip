@@ -7,6 +7,7 @@
 #include "../../include/vitq.h"
 #include "attention.h"
 #include "gemm.h"
+#include "gemm_f6.h"
 #include "layernorm.h"
 #include "quantize.h"
 
@@ -269,6 +270,48 @@ vq_status vq_linear_absorbed(const vq_qmat *xq, const vq_qmat *wq, const int32_t
     level_range(yq_out->bits, &p.qminf, &p.qmaxf);
     p.ab_bint = b_int; p.ab_thr = thr; p.ab_nthr = (1 << yq_out->bits) - 1;
     return gemm_launch(p, wq->storage_bits, xq->storage_bits, stream_) == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
+// ---- experimental 6-bit-float operand path ------------------------------------------------------
+vq_status vq_recode_e3m2_bytes(const vq_qmat *m, size_t *bytes) {
+    if (!bytes) return VQ_ERR_NULL;
+    vq_status st = check_qmat(m, 0);
+    if (st != VQ_OK) return st;
+    if (m->storage_bits != 4) return VQ_ERR_UNSUPPORTED;
+    *bytes = (size_t)(m->rows * f6_row_bytes(m->cols));
+    return VQ_OK;
+}
+
+vq_status vq_recode_e3m2(const vq_qmat *m, void *out, size_t out_bytes, void *stream) {
+    size_t need = 0;
+    vq_status st = vq_recode_e3m2_bytes(m, &need);
+    if (st != VQ_OK) return st;
+    if (need == 0) return VQ_OK;
+    if (!out) return VQ_ERR_NULL;
+    if (((uintptr_t)out) % 16 != 0) return VQ_ERR_STRIDE;
+    if (out_bytes < need) return VQ_ERR_WORKSPACE;
+    RecodeParams p{};
+    p.in = (const uint8_t *)m->data; p.in_stride = m->row_stride; p.in_row_bytes16 = (int)row_bytes16(m);
+    p.rows = m->rows; p.cols = m->cols;
+    p.out = (uint8_t *)out; p.out_stride = f6_row_bytes(m->cols);
+    return recode_e3m2_launch(p, (hipStream_t)stream) == hipSuccess ? VQ_OK : VQ_ERR_HIP;
+}
+
+vq_status vq_linear_e3m2(const void *x6, int64_t rows, const void *w6, int64_t out_features, int64_t cols,
+                         float s_x, const float *s_w, int32_t s_w_per_channel, const float *bias, float *y_out,
+                         void *stream) {
+    if (rows < 0 || out_features < 0 || cols <= 0 || cols > 65536) return VQ_ERR_SHAPE;
+    if (rows > INT32_MAX || out_features > INT32_MAX) return VQ_ERR_SHAPE;
+    if (!good_step(s_x)) return VQ_ERR_STEP;
+    if (rows == 0 || out_features == 0) return VQ_OK;
+    if (!x6 || !w6 || !s_w || !y_out) return VQ_ERR_NULL;
+    if (((uintptr_t)x6) % 16 != 0 || ((uintptr_t)w6) % 16 != 0 || ((uintptr_t)y_out) % 4 != 0) return VQ_ERR_STRIDE;
+    F6Params p{};
+    p.x = (const uint8_t *)x6; p.x_stride = f6_row_bytes(cols); p.M = (int)rows;
+    p.w = (const uint8_t *)w6; p.w_stride = f6_row_bytes(cols); p.Nout = (int)out_features;
+    p.K = (int)cols;
+    p.s_x = s_x; p.s_w = s_w; p.s_w_per_channel = s_w_per_channel ? 1 : 0; p.bias = bias; p.y_out = y_out;
+    return gemm_f6_launch(p, (hipStream_t)stream) == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }
 
 vq_status vq_layernorm_quantize(const float *x, const float *residual, float *sum_out, int64_t rows,

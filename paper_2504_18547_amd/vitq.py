@@ -19,7 +19,7 @@ EXPORTS = ["vq_status_string", "vq_weight_steps", "vq_quantize", "vq_linear", "v
            "vq_matmul_pv", "vq_attention_block_workspace", "vq_attention_block",
            "vq_prepack_weight_bytes", "vq_prepack_weight", "vq_linear_prepacked", "vq_layernorm_quantize",
            "vq_vit_block_workspace", "vq_vit_block", "vq_qkv_headnorm", "vq_absorb_thresholds",
-           "vq_linear_absorbed"]
+           "vq_linear_absorbed", "vq_recode_e3m2_bytes", "vq_recode_e3m2", "vq_linear_e3m2"]
 
 
 class VitqError(RuntimeError):
@@ -90,6 +90,9 @@ def lib():
                                              C.c_float, qp, vp]
         _lib.vq_absorb_thresholds.argtypes = [C.c_float, vp, C.c_int32, vp, C.c_int64, vp, C.c_int32, C.c_int32, vp, vp]
         _lib.vq_linear_absorbed.argtypes = [qp, qp, vp, vp, vp, qp, vp]
+        _lib.vq_recode_e3m2_bytes.argtypes = [qp, C.POINTER(C.c_size_t)]
+        _lib.vq_recode_e3m2.argtypes = [qp, vp, C.c_size_t, vp]
+        _lib.vq_linear_e3m2.argtypes = [vp, C.c_int64, vp, C.c_int64, C.c_int64, C.c_float, vp, C.c_int32, vp, vp, vp]
         _lib.vq_layernorm_quantize.argtypes = [vp, vp, vp, C.c_int64, C.c_int64, C.c_int64, vp, vp, C.c_float,
                                                C.c_float, qp, vp]
         _lib.vq_qkv_headnorm.argtypes = [vp, C.c_int64, C.c_int32, C.c_int32, C.c_int32, vp, vp, C.c_float,
@@ -231,6 +234,20 @@ def vq_absorb_thresholds(s_x, s_w, bias, s_y, bits):
 def vq_linear_absorbed(xq, wq, b_int, thr, acc_out, yq_out):
     _check(lib().vq_linear_absorbed(_q(xq), _q(wq), _ptr(b_int), _ptr(thr), _ptr(acc_out), _q(yq_out), _stream()),
            "vq_linear_absorbed")
+
+
+def vq_recode_e3m2(m):
+    """E3M2-coded copy of a packed matrix with 4-bit storage: a uint8 tensor [rows, ceil(cols/128)*96]."""
+    n = C.c_size_t(0)
+    _check(lib().vq_recode_e3m2_bytes(_q(m), C.byref(n)), "vq_recode_e3m2_bytes")
+    out = torch.empty(max(n.value, 16), dtype=torch.uint8, device=m.data.device)
+    _check(lib().vq_recode_e3m2(_q(m), _ptr(out), n.value, _stream()), "vq_recode_e3m2")
+    return out[:n.value].view(m.rows, -1) if m.rows else out[:0]
+
+
+def vq_linear_e3m2(x6, rows, w6, out_features, cols, s_x, s_w, s_w_per_channel, bias, y_out):
+    _check(lib().vq_linear_e3m2(_ptr(x6), rows, _ptr(w6), out_features, cols, float(s_x), _ptr(s_w),
+                                int(s_w_per_channel), _ptr(bias), _ptr(y_out), _stream()), "vq_linear_e3m2")
 
 
 def vq_matmul_qk(q, k, B, H, N, s_q, s_k, scale, s_acc_out, p_out):
