@@ -140,6 +140,44 @@ def test_host_side_argument_checks(lib):
     assert lib.vq_attention_block(C.byref(d), C.byref(xq), 2, fake, fake, 10, None) == E["VQ_ERR_SHAPE"]  # zeroed weight descriptors
 
 
+def test_host_side_argument_checks_of_the_later_entry_points(lib):
+    """Absorbed mode and the 6-bit-float path: every check below returns before any GPU call."""
+    from paper_2504_18547_amd import vitq
+    E = {n: i for i, n in enumerate(vitq.STATUS_NAMES)}
+    fake = C.c_void_p(0x2000)
+    f = C.c_float
+    x = _qm(vitq, 10, 64, 4, 4)
+    w = _qm(vitq, 16, 64, 4, 4)
+    yq = _qm(vitq, 10, 16, 4, 4)
+    ab = lambda *a: lib.vq_linear_absorbed(*a)
+    assert ab(C.byref(x), C.byref(w), None, None, None, C.byref(yq), None) == E["VQ_ERR_NULL"]        # no references
+    assert ab(C.byref(x), C.byref(w), None, fake, None, None, None) == E["VQ_ERR_NULL"]               # no output
+    assert ab(C.byref(x), C.byref(w), None, C.c_void_p(0x2002), None, C.byref(yq), None) == E["VQ_ERR_STRIDE"]
+    w24 = _qm(vitq, 24, 64, 4, 4)
+    yq24 = _qm(vitq, 10, 24, 4, 4)
+    assert ab(C.byref(x), C.byref(w24), None, fake, None, C.byref(yq24), None) == E["VQ_ERR_UNSUPPORTED"]   # 24 channels
+    yq2 = _qm(vitq, 10, 16, 2, 2)
+    assert ab(C.byref(x), C.byref(w), None, fake, None, C.byref(yq2), None) == E["VQ_ERR_UNSUPPORTED"]      # 2-bit storage
+    assert ab(C.byref(x), C.byref(w), None, fake, None, C.byref(_qm(vitq, 9, 16, 4, 4)), None) == E["VQ_ERR_SHAPE"]
+    x0 = _qm(vitq, 0, 64, 4, 4, data=None)
+    assert ab(C.byref(x0), C.byref(w), None, fake, None, C.byref(_qm(vitq, 0, 16, 4, 4, data=None)), None) == 0
+
+    n = C.c_size_t()
+    assert lib.vq_recode_e3m2_bytes(C.byref(x), C.byref(n)) == 0 and n.value == 10 * 96
+    assert lib.vq_recode_e3m2_bytes(C.byref(_qm(vitq, 3, 129, 3, 4)), C.byref(n)) == 0 and n.value == 3 * 192
+    assert lib.vq_recode_e3m2_bytes(C.byref(_qm(vitq, 3, 64, 8, 8)), C.byref(n)) == E["VQ_ERR_UNSUPPORTED"]
+    assert lib.vq_recode_e3m2_bytes(C.byref(x), None) == E["VQ_ERR_NULL"]
+    assert lib.vq_recode_e3m2(C.byref(x), fake, 10 * 96 - 1, None) == E["VQ_ERR_WORKSPACE"]
+    assert lib.vq_recode_e3m2(C.byref(x), None, 10 * 96, None) == E["VQ_ERR_NULL"]
+    assert lib.vq_recode_e3m2(C.byref(x), C.c_void_p(0x2008), 10 * 96, None) == E["VQ_ERR_STRIDE"]
+    lin = lambda *a: lib.vq_linear_e3m2(*a)
+    assert lin(fake, 10, fake, 16, 64, f(1.0), None, 1, None, fake, None) == E["VQ_ERR_NULL"]
+    assert lin(fake, 10, fake, 16, 0, f(1.0), fake, 1, None, fake, None) == E["VQ_ERR_SHAPE"]
+    assert lin(fake, 10, fake, 16, 64, f(0.0), fake, 1, None, fake, None) == E["VQ_ERR_STEP"]
+    assert lin(C.c_void_p(0x2004), 10, fake, 16, 64, f(1.0), fake, 1, None, fake, None) == E["VQ_ERR_STRIDE"]
+    assert lin(fake, 0, fake, 16, 64, f(1.0), fake, 1, None, fake, None) == 0
+
+
 def test_opcount_reproduces_table1():
     """Table I: PE and MAC counts of one head (N=198, I=384, O=64)."""
     from paper_2504_18547_amd import opcount
