@@ -94,22 +94,27 @@ __device__ __forceinline__ void wait_vmcnt_f6() {
     asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 
-constexpr int kTile = 128;          // tokens and channels per workgroup tile
 constexpr int kRowB = 96;           // bytes of one row in one stage (128 values)
 constexpr int kPieces = 6;          // 16-byte pieces per row and stage
-constexpr int kThreads = 256;
-constexpr int kStage = 2 * kTile * kRowB;                 // weights then tokens: 24576 bytes
-constexpr int kLoads = 2 * kTile * kPieces / kThreads;    // 6 loads per lane and stage
 
 __device__ __forceinline__ int rot_of(int row) { return (row >> 2) & 1; }
 
-template <int S, int OCC>
-__global__ __launch_bounds__(kThreads, OCC) void gemm_f6_kernel(F6Params p) {
+// TILE x TILE tokens x channels per workgroup, (TILE/64)^2 waves of 64 x 64 each, S stages in LDS.
+// (TILE = 256 with 16 waves and three stages was measured as well: same results, same time --
+// the kernel is bound by LDS reads per MFMA, not by operand delivery; 128 is what is launched.)
+template <int TILE, int S, int OCC>
+__global__ __launch_bounds__((TILE / 64) * (TILE / 64) * 64, OCC) void gemm_f6_kernel(F6Params p) {
+    constexpr int kTile = TILE;
+    constexpr int NWC = TILE / 64;                                // waves along the channels (and along the tokens)
+    constexpr int kThreads = NWC * NWC * 64;
+    constexpr int kStage = 2 * kTile * kRowB;                     // weights then tokens
+    constexpr int kLoads = 2 * kTile * kPieces / kThreads;        // loads per lane and stage
+    static_assert(2 * kTile * kPieces % kThreads == 0 && (kTile * kPieces) % 64 == 0, "tile / threads mismatch");
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wave_c = wave & 1, wave_t = wave >> 1;
+    const int wave_c = wave % NWC, wave_t = wave / NWC;
     const int li = lane & 31, kh = lane >> 5;
 
     // workgroups of one XCD walk consecutive tiles (they share that XCD's L2 copy of the tokens)
@@ -125,19 +130,21 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_f6_kernel(F6Params p) {
     const int t0 = (logical / n_ct) * kTile;
     const int nk = (p.K + 127) / 128;
 
-    // ---- what each lane fetches per stage: slot = it*256 + tid; slots 0..767 weights, 768.. tokens
+    // ---- what each lane fetches per stage: slot = it*threads + tid; the first kTile*6 slots are
+    // weight rows, the rest token rows (the boundary falls between waves, never inside one)
     const uint8_t *wbase = p.w + (int64_t)c0 * p.w_stride;
     const uint8_t *xbase = p.x + (int64_t)t0 * p.x_stride;
     u32 off[kLoads];
+    bool from_w[kLoads];                                        // wave-uniform
 #pragma unroll
     for (int it = 0; it < kLoads; ++it) {
-        const bool is_w = it < kLoads / 2;
-        const int slot = (it - (is_w ? 0 : kLoads / 2)) * kThreads + tid;
+        from_w[it] = it * kThreads + wave * 64 < kTile * kPieces;
+        const int slot = it * kThreads + tid - (from_w[it] ? 0 : kTile * kPieces);
         const int row = slot / kPieces, pos = slot - row * kPieces;
         const int piece = (pos + kPieces - rot_of(row)) % kPieces;
         // rows beyond the matrix are clamped to its last row: their sums are never stored
-        const int grow = is_w ? min(row, p.Nout - 1 - c0) : min(row, p.M - 1 - t0);
-        off[it] = (u32)grow * (u32)(is_w ? p.w_stride : p.x_stride) + (u32)piece * 16u;
+        const int grow = from_w[it] ? min(row, p.Nout - 1 - c0) : min(row, p.M - 1 - t0);
+        off[it] = (u32)grow * (u32)(from_w[it] ? p.w_stride : p.x_stride) + (u32)piece * 16u;
     }
     const u32 lds0 = __builtin_amdgcn_readfirstlane(lds_address_f6(smem)) + (u32)wave * 1024u;
     auto issue = [&](int kt) {
@@ -146,7 +153,7 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_f6_kernel(F6Params p) {
         const uint8_t *xk = xbase + (int64_t)kt * kRowB;
 #pragma unroll
         for (int it = 0; it < kLoads; ++it)
-            dma16_f6(off[it], it < kLoads / 2 ? wk : xk, dst + it * (kThreads * 16));
+            dma16_f6(off[it], from_w[it] ? wk : xk, dst + it * (kThreads * 16));
     };
 #pragma unroll
     for (int st = 0; st < S - 1; ++st)
@@ -239,15 +246,16 @@ __global__ __launch_bounds__(kThreads, OCC) void gemm_f6_kernel(F6Params p) {
     }
 }
 
-template <int S, int OCC>
+template <int TILE, int S, int OCC>
 hipError_t launch_f6(const F6Params &p, hipStream_t stream) {
-    constexpr size_t lds = (size_t)S * kStage;
-    auto kern = gemm_f6_kernel<S, OCC>;
+    constexpr size_t lds = (size_t)S * 2 * TILE * kRowB;
+    constexpr int threads = (TILE / 64) * (TILE / 64) * 64;
+    auto kern = gemm_f6_kernel<TILE, S, OCC>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    const int64_t blocks = (int64_t)((p.Nout + kTile - 1) / kTile) * ((p.M + kTile - 1) / kTile);
-    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kThreads), lds, stream, p);
+    const int64_t blocks = (int64_t)((p.Nout + TILE - 1) / TILE) * ((p.M + TILE - 1) / TILE);
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(threads), lds, stream, p);
     return hipGetLastError();
 }
 
@@ -265,9 +273,9 @@ hipError_t recode_e3m2_launch(const RecodeParams &p, hipStream_t stream) {
 #define VITQ_F6_OCC 3
 #endif
 hipError_t gemm_f6_launch(const F6Params &p, hipStream_t stream) {
-    // per-lane operand offsets inside a tile are kept in 32 bits (127 rows * stride + 80)
-    if (p.M < 1 || p.Nout < 1 || p.K < 1 || p.x_stride >= (1 << 24) || p.w_stride >= (1 << 24)) return hipErrorInvalidValue;
-    return launch_f6<VITQ_F6_S, VITQ_F6_OCC>(p, stream);
+    // per-lane operand offsets inside a tile are kept in 32 bits (255 rows * stride + 80)
+    if (p.M < 1 || p.Nout < 1 || p.K < 1 || p.x_stride >= (1 << 23) || p.w_stride >= (1 << 23)) return hipErrorInvalidValue;
+    return launch_f6<128, VITQ_F6_S, VITQ_F6_OCC>(p, stream);
 }
 
 }  // namespace vitq
