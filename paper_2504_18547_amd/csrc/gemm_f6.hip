@@ -101,7 +101,7 @@ __device__ __forceinline__ int rot_of(int row) { return (row >> 2) & 1; }
 
 // TILE x TILE tokens x channels per workgroup, (TILE/64)^2 waves of 64 x 64 each, S stages in LDS.
 // (TILE = 256 with 16 waves and three stages was measured as well: same results, same time --
-// the kernel is bound by LDS reads per MFMA, not by operand delivery; 128 is what is launched.)
+// the bytes moved are not what bounds the kernel; 128 is what is launched.)
 template <int TILE, int S, int OCC>
 __global__ __launch_bounds__((TILE / 64) * (TILE / 64) * 64, OCC) void gemm_f6_kernel(F6Params p) {
     constexpr int kTile = TILE;
