@@ -416,16 +416,16 @@ __device__ __forceinline__ void epilogue_headnorm(const GemmParams &p, v16i (&ac
 // ---- integer-only epilogue: equivalent bias + comparator references with the scales absorbed ----
 // (Eq. 2, second form; Sec. IV-B.)  level = qmin + #{t : acc + b_int[c] > T[c][t]}, T non-decreasing
 // in t, so the count is found by bisection: 4 integer comparisons for up to 15 references, 8 for up
-// to 255, no branch, no floating point.  tbl: the tile's references in LDS, rows of kAbsRow entries
-// (INT32_MAX -- never exceeded -- beyond the last one), or, with more than 15 per channel, the
-// caller's table in global memory.
+// to 255, no branch, no floating point.  The tile keeps rows of kAbsRow entries in LDS (INT32_MAX
+// -- never exceeded -- beyond the last reference): the references themselves when there are at
+// most 15 per channel, else every sixteenth one (T[15], T[31], ...), which settles the first four
+// strides; the last four then probe one 16-entry stretch of the caller's table in global memory.
 constexpr int kAbsRow = 17;
 template <bool TBL_LDS>
 __device__ __forceinline__ void epilogue_absorbed(const GemmParams &p, const v16i &acc, int shift, uint8_t *dst,
-                                                  const int *tbl, int64_t tbl_row, const int *bint) {
+                                                  const int *lds_tbl, const int *glb_tbl, int64_t glb_row, const int *bint) {
     if (!dst) return;
     const int nthr = p.ab_nthr;
-    constexpr int TOP = TBL_LDS ? 8 : 128;             // first bisection stride: 2^(steps-1)
     float lv[16];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -436,21 +436,26 @@ __device__ __forceinline__ void epilogue_absorbed(const GemmParams &p, const v16
             const int r = 4 * q + i;
             const int a = (acc[r] >> shift) + bq[i];
             int pos = 0;                                // references known to be exceeded
+            if constexpr (TBL_LDS) {
 #pragma unroll
-            for (int step = TOP; step >= 1; step >>= 1) {
-                const int t = pos + step - 1;
-                int ref;
-                if constexpr (TBL_LDS) {
-                    ref = tbl[r * kAbsRow + t];
-                } else {
-                    const int v = tbl[(int64_t)r * tbl_row + min(t, nthr - 1)];
-                    ref = t >= nthr ? INT32_MAX : v;
+                for (int step = 8; step >= 1; step >>= 1)
+                    pos += (a > lds_tbl[r * kAbsRow + pos + step - 1]) ? step : 0;
+            } else {
+                // strides 128..16 probe T[16(i+1) - 1]: entry i of the LDS row; strides 8..1 finish
+                // inside one 16-entry stretch of the caller's table
+#pragma unroll
+                for (int step = 128; step >= 16; step >>= 1)
+                    pos += (a > lds_tbl[r * kAbsRow + ((pos + step) >> 4) - 1]) ? step : 0;
+#pragma unroll
+                for (int step = 8; step >= 1; step >>= 1) {
+                    const int t = pos + step - 1;
+                    const int v = glb_tbl[(int64_t)r * glb_row + min(t, nthr - 1)];
+                    pos += (a > (t >= nthr ? INT32_MAX : v)) ? step : 0;
                 }
-                pos += (a > ref) ? step : 0;
             }
             lv[r] = (float)pos;
         }
-        if constexpr (TBL_LDS) __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_sched_barrier(0);
     }
     pack_store16(p, dst, lv, -p.qminf);
 }
@@ -606,18 +611,17 @@ void gemm_kernel(GemmParams p) {
     // Integer-only epilogue: this lane's share of the tile's comparator references is requested
     // now, ahead of every operand load (loads retire in order, so the hand-counted waits of the
     // main loop are unaffected), and parked in registers until the pipeline buffers are free.
-    constexpr int ABS_ITERS = (EPI == kEpiAbsorbed) ? (TC * kAbsRow + NT - 1) / NT : 1;
+    constexpr int ABS_ITERS = ABSORBED ? (TC * kAbsRow + NT - 1) / NT : 1;
     [[maybe_unused]] int abs_ref[ABS_ITERS];
-    if constexpr (EPI == kEpiAbsorbed) {
+    if constexpr (ABSORBED) {
         const int nthr = p.ab_nthr;
-        {
 #pragma unroll
-            for (int k = 0; k < ABS_ITERS; ++k) {
-                const int i = min(k * NT + tid, TC * kAbsRow - 1);
-                const int c = i / kAbsRow, t = i - kAbsRow * c;          // entry t of channel c
-                const int ch = min(c0 + c, p.Nout - 1);
-                abs_ref[k] = p.ab_thr[(int64_t)ch * nthr + min(t, nthr - 1)];           // (pads: replaced when stored)
-            }
+        for (int k = 0; k < ABS_ITERS; ++k) {
+            const int i = min(k * NT + tid, TC * kAbsRow - 1);
+            const int c = i / kAbsRow, e = i - kAbsRow * c;              // entry e of channel c
+            const int t = (EPI == kEpiAbsorbed) ? e : 16 * (e + 1) - 1;  // the reference it holds
+            const int ch = min(c0 + c, p.Nout - 1);
+            abs_ref[k] = p.ab_thr[(int64_t)ch * nthr + min(t, nthr - 1)];               // (pads: replaced when stored)
         }
     }
 #pragma unroll
@@ -821,21 +825,19 @@ void gemm_kernel(GemmParams p) {
             }
         }
         if constexpr (ABSORBED) {
-            // The pipeline buffers are free now: with at most 15 references per channel the tile's
-            // table is copied into them (padded rows, see epilogue_absorbed), larger tables are read in place.
+            // The pipeline buffers are free now: the tile's LDS table (see epilogue_absorbed) goes there.
             const int nthr = p.ab_nthr;
             constexpr bool in_lds = (EPI == kEpiAbsorbed);
             int *s_tbl = reinterpret_cast<int *>(smem);
             static_assert(TC * kAbsRow * 4 <= S * STAGE, "reference table exceeds the pipeline buffers");
-            if constexpr (in_lds) {
 #pragma unroll
-                for (int k = 0; k < ABS_ITERS; ++k) {
-                    const int i = k * NT + tid;
-                    const int t = i % kAbsRow;
-                    if (i < TC * kAbsRow) s_tbl[i] = t >= nthr ? INT32_MAX : abs_ref[k];
-                }
-                __syncthreads();
+            for (int k = 0; k < ABS_ITERS; ++k) {
+                const int i = k * NT + tid;
+                const int e = i % kAbsRow;
+                const int t = in_lds ? e : 16 * (e + 1) - 1;
+                if (i < TC * kAbsRow) s_tbl[i] = t >= nthr ? INT32_MAX : abs_ref[k];
             }
+            __syncthreads();
             int64_t tok_part[NTK];
 #pragma unroll
             for (int ti = 0; ti < NTK; ++ti) tok_part[ti] = packed_token_part(p, t0 + wave_t * WT + ti * 32 + li);
@@ -851,11 +853,9 @@ void gemm_kernel(GemmParams p) {
                     uint8_t *dst = (ch_part >= 0 && tok_part[ti] >= 0) ? p.yq + tok_part[ti] + ch_part : nullptr;
                     if (cb >= p.Nout)
                         store_zero_group(p, dst);
-                    else if constexpr (in_lds)
-                        epilogue_absorbed<true>(p, acc[ci][ti], shift, dst, s_tbl + cl * kAbsRow, kAbsRow, bint);
                     else
-                        epilogue_absorbed<false>(p, acc[ci][ti], shift, dst, p.ab_thr + (int64_t)min(cb, p.Nout - 16) * nthr,
-                                                 nthr, bint);
+                        epilogue_absorbed<in_lds>(p, acc[ci][ti], shift, dst, s_tbl + cl * kAbsRow,
+                                                  p.ab_thr + (int64_t)min(cb, p.Nout - 16) * nthr, nthr, bint);
                 });
             });
             return;

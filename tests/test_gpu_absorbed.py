@@ -52,6 +52,9 @@ def _run(xq, wq, b_int, thr, bits_w, bits_a, bits_y, want_acc=True):
     (8, 8, 8, 150, 320, 64),        # 255 references per channel: read from global memory
     (8, 8, 4, 129, 64, 160),
     (4, 4, 8, 40, 128, 32),
+    (8, 8, 6, 70, 128, 32),         # 63 references: both levels of the two-level table end early
+    (4, 4, 5, 33, 256, 48),         # 31 references
+    (8, 8, 7, 20, 64, 16),          # 127 references
 ])
 def test_against_oracle(bits_w, bits_a, bits_y, M, K, Nout):
     xq, wq, s_w, bias = _operands(1000 + M + bits_y, M, K, Nout, bits_w, bits_a)
