@@ -322,11 +322,24 @@ typedef struct vq_preln_desc {
 vq_status vq_vit_block_workspace(const vq_preln_desc *desc, int64_t B, size_t *bytes);
 
 /*
- * x: device fp32 [B*N x D], 16-byte aligned, not aliasing y_out.  y_out: device fp32 [B*N x D]
- * (holds x1 between the stages).  workspace: device, 256-byte aligned.
+ * x: device fp32 [B*N x D], 16-byte aligned.  y_out: device fp32 [B*N x D] (holds x1 between the
+ * stages); it may be x itself (the block then updates the stream in place: x is last read, as
+ * the residual, by the very lanes that write x1 over it) but must not overlap it otherwise
+ * (VQ_ERR_STRIDE).  workspace: device, 256-byte aligned.
  */
 vq_status vq_vit_block(const vq_preln_desc *desc, const float *x, int64_t B, float *y_out,
                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * A stack of such blocks (an encoder: the paper's model is twelve of them): layer 0 reads x and
+ * writes y_out, every further layer updates y_out in place.  layers: HOST array of n_layers
+ * descriptors that agree in D, H, N, bit widths and storage (else VQ_ERR_SHAPE); the dump
+ * pointers of the descriptors are honoured per layer.  The workspace is shared by the layers:
+ * vq_vit_encoder_workspace reports the largest need.  x may be y_out (as above).
+ */
+vq_status vq_vit_encoder_workspace(const vq_preln_desc *layers, int32_t n_layers, int64_t B, size_t *bytes);
+vq_status vq_vit_encoder(const vq_preln_desc *layers, int32_t n_layers, const float *x, int64_t B,
+                         float *y_out, void *workspace, size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus
 }

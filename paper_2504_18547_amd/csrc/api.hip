@@ -710,7 +710,12 @@ vq_status vq_vit_block(const vq_preln_desc *desc, const float *x, int64_t B, flo
     if (!desc->ln1_gamma || !desc->ln1_beta || !desc->ln2_gamma || !desc->ln2_beta) return VQ_ERR_NULL;
     if (B == 0) return VQ_OK;
     if (!x || !y_out) return VQ_ERR_NULL;
-    if (x == y_out) return VQ_ERR_NULL;                   // the input stream is read again after y is written
+    {   // in place is fine (x is last read as the residual, element by element, by the lane that then
+        // writes x1 there); any other overlap is not
+        const uintptr_t xa = (uintptr_t)x, ya = (uintptr_t)y_out;
+        const uintptr_t bytes = (uintptr_t)L.M * (uintptr_t)d->D * sizeof(float);
+        if (xa != ya && xa < ya + bytes && ya < xa + bytes) return VQ_ERR_STRIDE;
+    }
     const size_t xq_bytes = align256((size_t)(L.M * L.act_row));
     if (!workspace || workspace_bytes < L.total + xq_bytes) return VQ_ERR_WORKSPACE;
     if (((uintptr_t)workspace) % 256 != 0) return VQ_ERR_WORKSPACE;
@@ -767,6 +772,37 @@ vq_status vq_vit_block(const vq_preln_desc *desc, const float *x, int64_t B, flo
     if (st != VQ_OK) return st;
     return run_linear(&hq, d->s_h, &d->w_fc2, d->sw_fc2, 1, d->b_fc2, 0, nullptr, y_out, 0.0f, nullptr, nullptr,
                       stream, d->wp_fc2, y_out);
+}
+
+vq_status vq_vit_encoder_workspace(const vq_preln_desc *layers, int32_t n_layers, int64_t B, size_t *bytes) {
+    if (!layers || !bytes) return VQ_ERR_NULL;
+    if (n_layers < 1) return VQ_ERR_SHAPE;
+    size_t need = 0;
+    for (int32_t i = 0; i < n_layers; ++i) {
+        size_t n = 0;
+        vq_status st = vq_vit_block_workspace(&layers[i], B, &n);
+        if (st != VQ_OK) return st;
+        need = n > need ? n : need;
+        const vq_block_desc &a = layers[0].block, &b = layers[i].block;
+        if (a.D != b.D || a.H != b.H || a.N != b.N || a.bits_a != b.bits_a || a.bits_p != b.bits_p ||
+            a.storage_a != b.storage_a)
+            return VQ_ERR_SHAPE;
+    }
+    *bytes = need;
+    return VQ_OK;
+}
+
+vq_status vq_vit_encoder(const vq_preln_desc *layers, int32_t n_layers, const float *x, int64_t B, float *y_out,
+                         void *workspace, size_t workspace_bytes, void *stream) {
+    size_t need = 0;
+    vq_status st = vq_vit_encoder_workspace(layers, n_layers, B, &need);
+    if (st != VQ_OK) return st;
+    if (workspace_bytes < need) return VQ_ERR_WORKSPACE;
+    for (int32_t i = 0; i < n_layers; ++i) {
+        st = vq_vit_block(&layers[i], i == 0 ? x : y_out, B, y_out, workspace, workspace_bytes, stream);
+        if (st != VQ_OK) return st;
+    }
+    return VQ_OK;
 }
 
 }  // extern "C"

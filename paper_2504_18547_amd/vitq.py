@@ -19,7 +19,7 @@ EXPORTS = ["vq_status_string", "vq_weight_steps", "vq_quantize", "vq_linear", "v
            "vq_matmul_pv", "vq_attention_block_workspace", "vq_attention_block",
            "vq_prepack_weight_bytes", "vq_prepack_weight", "vq_linear_prepacked", "vq_layernorm_quantize",
            "vq_vit_block_workspace", "vq_vit_block", "vq_qkv_headnorm", "vq_absorb_thresholds",
-           "vq_linear_absorbed", "vq_recode_e3m2_bytes", "vq_recode_e3m2", "vq_linear_e3m2"]
+           "vq_linear_absorbed", "vq_recode_e3m2_bytes", "vq_recode_e3m2", "vq_linear_e3m2", "vq_vit_encoder_workspace", "vq_vit_encoder"]
 
 
 class VitqError(RuntimeError):
@@ -99,6 +99,8 @@ def lib():
                                          C.c_float, C.c_float, C.c_float, C.c_int32, C.c_int32, vp, vp]
         _lib.vq_vit_block_workspace.argtypes = [C.POINTER(vq_preln_desc), C.c_int64, C.POINTER(C.c_size_t)]
         _lib.vq_vit_block.argtypes = [C.POINTER(vq_preln_desc), vp, C.c_int64, vp, vp, C.c_size_t, vp]
+        _lib.vq_vit_encoder_workspace.argtypes = [C.POINTER(vq_preln_desc), C.c_int32, C.c_int64, C.POINTER(C.c_size_t)]
+        _lib.vq_vit_encoder.argtypes = [C.POINTER(vq_preln_desc), C.c_int32, vp, C.c_int64, vp, vp, C.c_size_t, vp]
         for n in EXPORTS[1:]:
             getattr(_lib, n).restype = C.c_int
     return _lib
@@ -326,3 +328,23 @@ def vq_vit_block(desc, x, B, y_out, workspace):
     _check(lib().vq_vit_block(C.byref(desc), _ptr(x), int(B), _ptr(y_out), _ptr(workspace),
                               workspace.numel() * workspace.element_size() if workspace is not None else 0,
                               _stream()), "vq_vit_block")
+
+
+def _layer_array(descs):
+    arr = (vq_preln_desc * len(descs))()
+    for i, d in enumerate(descs):
+        C.memmove(C.byref(arr[i]), C.byref(d), C.sizeof(vq_preln_desc))
+    return arr
+
+
+def vq_vit_encoder_workspace(descs, B):
+    n = C.c_size_t()
+    _check(lib().vq_vit_encoder_workspace(_layer_array(descs), len(descs), int(B), C.byref(n)), "vq_vit_encoder_workspace")
+    return n.value
+
+
+def vq_vit_encoder(descs, x, B, y_out, workspace):
+    """descs: list of vq_preln_desc, one per layer (the tensors they point to must stay alive)."""
+    _check(lib().vq_vit_encoder(_layer_array(descs), len(descs), _ptr(x), int(B), _ptr(y_out), _ptr(workspace),
+                                workspace.numel() * workspace.element_size() if workspace is not None else 0,
+                                _stream()), "vq_vit_encoder")

@@ -72,7 +72,7 @@ def test_vit_b_block_reduced_batch():
     _run("vit_b_block", [0, 1, 2], True, 4, 4, dumps=True)
 
 
-def test_aliasing_and_missing_layernorm_parameters_are_rejected():
+def test_missing_layernorm_parameters_are_rejected():
     c = preln_case("tiny_block", True, 4, 4, [0])
     dims, st = c["dims"], c["st"]
     wd = device_weights(c["wts"], 4)
@@ -82,9 +82,6 @@ def test_aliasing_and_missing_layernorm_parameters_are_rejected():
     desc = vitq.make_preln_desc(blk, lnd)
     ws = torch.empty(vitq.vq_vit_block_workspace(desc, 1), dtype=torch.uint8, device="cuda")
     x = dev(c["x"])
-    with pytest.raises(vitq.VitqError) as e:
-        vitq.vq_vit_block(desc, x, 1, x, ws)
-    assert e.value.status == vitq.STATUS_NAMES.index("VQ_ERR_NULL")
     desc.ln2_beta = None
     y = torch.zeros_like(x)
     with pytest.raises(vitq.VitqError) as e:
@@ -92,3 +89,62 @@ def test_aliasing_and_missing_layernorm_parameters_are_rejected():
     assert e.value.status == vitq.STATUS_NAMES.index("VQ_ERR_NULL")
     torch.cuda.synchronize()
     assert torch.all(y == 0)
+
+
+def _layer(c, bits_w, bits_a, keep):
+    """Descriptor of one encoder layer from a preln_case; the device tensors go into `keep` (the
+    descriptor only holds raw pointers)."""
+    sa = storage_of(bits_a)
+    wd = device_weights(c["wts"], bits_w)
+    lnd = {k: dev(v) for k, v in c["ln"].items() if k != "eps"}
+    lnd["eps"] = c["ln"]["eps"]
+    blk = vitq.make_block_desc(c["dims"], bits_a, bits_a, sa, wd, c["st"])
+    keep.append((wd, lnd, blk))
+    return vitq.make_preln_desc(blk, lnd)
+
+
+def test_encoder_of_three_layers_and_in_place_stream():
+    images = [0, 1]
+    cases = [preln_case("tiny_block", sharp, 4, 4, images) for sharp in (False, True, False)]
+    dims = cases[0]["dims"]
+    B, N, D = len(images), dims["N"], dims["D"]
+    x = cases[0]["x"]
+    h = x
+    for c in cases:                                   # the oracle, layer by layer
+        h = vqo.vit_block_preln(h, B, dims, c["wts"], c["st"], c["ln"], bits_a=4, bits_p=4)["y"]
+    keep = []
+    descs = [_layer(c, 4, 4, keep) for c in cases]
+    ws = torch.empty(vitq.vq_vit_encoder_workspace(descs, B), dtype=torch.uint8, device="cuda")
+    xd = dev(x)
+    y = torch.full((B * N, D), -9.0, dtype=torch.float32, device="cuda")
+    vitq.vq_vit_encoder(descs, xd, B, y, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(y.cpu().numpy(), h)
+    assert torch.equal(xd.cpu(), torch.from_numpy(x))
+    # the same stack updating the stream in place
+    vitq.vq_vit_encoder(descs, xd, B, xd, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(xd.cpu().numpy(), h)
+    # one block in place as well
+    xd2 = dev(x)
+    vitq.vq_vit_block(descs[0], xd2, B, xd2, ws)
+    torch.cuda.synchronize()
+    first = vqo.vit_block_preln(x, B, dims, cases[0]["wts"], cases[0]["st"], cases[0]["ln"], bits_a=4, bits_p=4)["y"]
+    assert np.array_equal(xd2.cpu().numpy(), first)
+
+
+def test_partly_overlapping_streams_and_mismatched_layers_are_rejected():
+    c = preln_case("tiny_block", False, 4, 4, [0, 1])
+    dims = c["dims"]
+    B, N, D = 2, dims["N"], dims["D"]
+    keep = []
+    desc = _layer(c, 4, 4, keep)
+    ws = torch.empty(vitq.vq_vit_block_workspace(desc, B), dtype=torch.uint8, device="cuda")
+    buf = torch.zeros((B * N + 4, D), dtype=torch.float32, device="cuda")
+    with pytest.raises(vitq.VitqError) as e:
+        vitq.vq_vit_block(desc, buf[:B * N], B, buf[4:], ws)
+    assert e.value.status == vitq.STATUS_NAMES.index("VQ_ERR_STRIDE")
+    other = _layer(preln_case("tiny_long", False, 4, 4, [0]), 4, 4, keep)
+    with pytest.raises(vitq.VitqError) as e:
+        vitq.vq_vit_encoder_workspace([desc, other], B)
+    assert e.value.status == vitq.STATUS_NAMES.index("VQ_ERR_SHAPE")
