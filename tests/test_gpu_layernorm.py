@@ -118,3 +118,21 @@ def test_bad_arguments_leave_output_untouched():
         assert e.value.status == vitq.STATUS_NAMES.index("VQ_ERR_STEP")
     torch.cuda.synchronize()
     assert torch.all(out.data == 0x5A)
+
+
+def test_every_binary_exponent_of_the_input_scale():
+    # one row per power of two from 2^-140 to 2^126: the kernel's division-free mean update is only
+    # used while the deviations are ordinary numbers, and must hand over to the division outside
+    # that range without a visible seam (both sides overflow and underflow alike)
+    rng = np.random.default_rng(77)
+    exps = np.arange(-140, 127)
+    cols = 200
+    base = rng.standard_normal((len(exps), cols)).astype(np.float32)
+    with np.errstate(over="ignore", under="ignore"):
+        x = (base.astype(np.float64) * np.exp2(exps.astype(np.float64))[:, None]).astype(np.float32)
+    x[5, 10:60] = 0.0                          # exact zero deviations inside a tiny row
+    x[200, 3] = x[200, 4]                      # a repeated value
+    gamma = rng.uniform(0.5, 1.5, cols).astype(np.float32)
+    beta = rng.normal(0, 0.3, cols).astype(np.float32)
+    for eps in (0.0, 1e-6):
+        _check(x, gamma, beta, eps, np.float32(0.4), 4)
