@@ -40,3 +40,15 @@ def test_every_benchmark_workload_has_steps():
         for sharp in (False, True):
             st = wl.block_steps(name, sharp, bw, ba)
             assert all(np.isfinite(v) and v > 0 for v in st.values())
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # the path runs on one GPU; asking for more must end with a message, before anything touches a GPU
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
