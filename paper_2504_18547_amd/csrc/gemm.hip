@@ -20,6 +20,7 @@
 // operation sequence.  The result is therefore always the definition's, bit for bit.
 #include "gemm.h"
 #include <type_traits>
+#include "launch_util.h"
 #include "vitq_dev.h"
 
 namespace vitq {
@@ -911,8 +912,8 @@ hipError_t launch(const GemmParams &p, hipStream_t stream) {
                            (EPI == kEpiHeadNorm ? 2 * TC * sizeof(float) : 0);
     auto kern = gemm_kernel<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, S, OCC, EPI>;
     if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        static std::atomic<uint64_t> allowed{0};        // (one per instantiation)
+        hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds, allowed);
         if (e != hipSuccess) return e;
     }
     const int n_ct = (p.Nout + TC - 1) / TC;

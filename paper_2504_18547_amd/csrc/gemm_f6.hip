@@ -32,6 +32,7 @@
 // MFMA roles: tokens on the A side, weight rows on the B side, so that register r of the wave
 // is 32 consecutive channels (a 128-byte line) of one token, as in the int8 kernel's fp32 epilogue.
 #include "gemm_f6.h"
+#include "launch_util.h"
 #include "vitq_dev.h"
 
 namespace vitq {
@@ -251,8 +252,8 @@ hipError_t launch_f6(const F6Params &p, hipStream_t stream) {
     constexpr size_t lds = (size_t)S * 2 * TILE * kRowB;
     constexpr int threads = (TILE / 64) * (TILE / 64) * 64;
     auto kern = gemm_f6_kernel<TILE, S, OCC>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    static std::atomic<uint64_t> allowed{0};            // (one per instantiation)
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(kern), lds, allowed);
     if (e != hipSuccess) return e;
     const int64_t blocks = (int64_t)((p.Nout + TILE - 1) / TILE) * ((p.M + TILE - 1) / TILE);
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(threads), lds, stream, p);
