@@ -299,6 +299,25 @@ vq_status vq_attention_block(const vq_block_desc *desc, const vq_qmat *xq, int64
                              void *stream);
 
 /*
+ * vq_attention_block for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, checks, kernels and results as vq_attention_block, but the intermediates (packed
+ * Q/K/V, O, X2, H) live in an array of VQ_STATIC_SCRATCH_BYTES bytes that is part of the
+ * library's device code: every GPU the library runs on holds one copy until the process ends.
+ * The call allocates and frees nothing (no hipMalloc / hipFree, no allocating runtime routine);
+ * the array's device address is looked up once per device, on the first call there.
+ * Limits: vq_attention_block_workspace(desc, B) must not exceed VQ_STATIC_SCRATCH_BYTES (else
+ * VQ_ERR_WORKSPACE, nothing launched; e.g. ViT-S attention up to B = 110, the ViT-B block up to
+ * B = 24); desc->qk_gamma must be NULL (VQ_ERR_UNSUPPORTED).  All calls on one GPU share that
+ * GPU's array, which keeps the previous call's contents (every byte a stage reads is written by
+ * the stage before it, so nothing needs clearing): calls that overlap in time on one GPU -- two
+ * streams, two threads -- race and must be serialised by the caller.
+ */
+#define VQ_STATIC_SCRATCH_BYTES (16u << 20)
+vq_status vq_attention_block_static(const vq_block_desc *desc, const vq_qmat *xq, int64_t B,
+                                    float *y_out, void *stream);
+
+/*
  * A whole pre-LayerNorm ViT block on the fp32 residual stream, built from the stages above
  * (the LayerNorm quantizer of Sec. IV-C in front of the integerized attention of Sec. III-IV and,
  * by the same principle, in front of the MLP):

@@ -1,8 +1,11 @@
 // C ABI of libvitq.so: argument validation on the host, then kernel launches.
-// No allocation, no synchronization, no global state.
+// No allocation, no synchronization; the only state is the per-device address of the static
+// scratch array that vq_attention_block_static uses.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
+
+#include <atomic>
 
 #include "../../include/vitq.h"
 #include "attention.h"
@@ -14,6 +17,8 @@
 using namespace vitq;
 
 namespace {
+
+constexpr int kMaxDevices = 64;
 
 bool good_step(float s) { return isfinite(s) && s > 0.0f; }
 
@@ -612,8 +617,11 @@ vq_status vq_attention_block_workspace(const vq_block_desc *desc, int64_t B, siz
     return VQ_OK;
 }
 
-vq_status vq_attention_block(const vq_block_desc *d, const vq_qmat *xq, int64_t B, float *y_out,
-                             void *workspace, size_t workspace_bytes, void *stream_) {
+namespace {
+
+// Body of both block entry points: every check on the host first, then the launches.
+vq_status run_attention_block(const vq_block_desc *d, const vq_qmat *xq, int64_t B, float *y_out,
+                              void *workspace, size_t workspace_bytes, void *stream_) {
     BlockLayout L;
     vq_status st = block_check(d, B, &L);
     if (st != VQ_OK) return st;
@@ -682,6 +690,44 @@ vq_status vq_attention_block(const vq_block_desc *d, const vq_qmat *xq, int64_t 
                     stream, d->wp_fc2);
     mark();
     return st;
+}
+
+// The intermediates of vq_attention_block_static (packed Q/K/V, O, X2, H): one array per GPU, held
+// until the process ends.  The name below is a host-side handle only; the device address comes
+// from hipGetSymbolAddress, once per device, and that pointer is what the kernels receive.
+static __device__ __align__(256) unsigned char scratch[VQ_STATIC_SCRATCH_BYTES];
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+vq_status static_scratch(void **out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return VQ_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return VQ_ERR_UNSUPPORTED;
+    void *ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return VQ_ERR_HIP;
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);     // (racing first calls store the same address)
+    }
+    *out = ptr;
+    return VQ_OK;
+}
+
+}  // namespace
+
+vq_status vq_attention_block(const vq_block_desc *d, const vq_qmat *xq, int64_t B, float *y_out,
+                             void *workspace, size_t workspace_bytes, void *stream) {
+    return run_attention_block(d, xq, B, y_out, workspace, workspace_bytes, stream);
+}
+
+vq_status vq_attention_block_static(const vq_block_desc *d, const vq_qmat *xq, int64_t B, float *y_out,
+                                    void *stream) {
+    BlockLayout L;
+    vq_status st = block_check(d, B, &L);
+    if (st != VQ_OK) return st;
+    if (d->qk_gamma) return VQ_ERR_UNSUPPORTED;                   // (its fallback stages an fp32 QKV matrix)
+    if (L.total > (size_t)VQ_STATIC_SCRATCH_BYTES) return VQ_ERR_WORKSPACE;
+    void *ws = nullptr;
+    if ((st = static_scratch(&ws)) != VQ_OK) return st;
+    return run_attention_block(d, xq, B, y_out, ws, (size_t)VQ_STATIC_SCRATCH_BYTES, stream);
 }
 
 vq_status vq_vit_block_workspace(const vq_preln_desc *desc, int64_t B, size_t *bytes) {
