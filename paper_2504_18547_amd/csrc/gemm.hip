@@ -27,6 +27,12 @@ namespace vitq {
 
 namespace {
 
+#ifndef VITQ_TC
+#define VITQ_TC 128
+#define VITQ_TT 256
+#define VITQ_S44 3
+#define VITQ_OCC44 2
+#endif
 #ifndef VITQ_BK88
 #define VITQ_BK88 64
 #define VITQ_S88 3
@@ -319,8 +325,8 @@ __device__ __forceinline__ void epilogue_quant(const GemmParams &p, const v16i &
 // picks which two comparisons are evaluated).  The fp32 linear output never leaves registers.
 // gamma / beta / the folded scales are wave-uniform: staged in LDS once per tile and read as
 // broadcasts.
-template <int SB>
-__device__ __forceinline__ void epilogue_headnorm(const GemmParams &p, v16i (&acc)[2][2], int shift, uint8_t *dst,
+template <int SB, int NTK, int PAIR>   // PAIR: token blocks 2*PAIR and 2*PAIR + 1 of the wave's NTK
+__device__ __forceinline__ void epilogue_headnorm(const GemmParams &p, v16i (&acc)[2][NTK], int shift, uint8_t *dst,
                                                   const float *scs64, const float *bs64, float step,
                                                   const float *gp, const float *bp) {
     // trade halves: afterwards sw[0] is channel 32*ci + r and sw[1] channel 32*ci + 16 + r of this
@@ -332,7 +338,7 @@ __device__ __forceinline__ void epilogue_headnorm(const GemmParams &p, v16i (&ac
     for (int ci = 0; ci < 2; ++ci) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const auto sw = __builtin_amdgcn_permlane32_swap(acc[ci][0][r], acc[ci][1][r], false, false);
+            const auto sw = __builtin_amdgcn_permlane32_swap(acc[ci][2 * PAIR][r], acc[ci][2 * PAIR + 1][r], false, false);
             v[32 * ci + r] = to_y((int)sw[0], 32 * ci + r);
             v[32 * ci + 16 + r] = to_y((int)sw[1], 32 * ci + 16 + r);
         }
@@ -506,6 +512,13 @@ __device__ __forceinline__ int channel_of_slot(int s) {
     return 16 * ((s >> 2) & 1) + 4 * (s >> 3) + (s & 3);
 }
 
+// marks every fragment of a set as used (and possibly modified) here: an anchor for the scheduler
+template <int N>
+__device__ __forceinline__ void pin_frags(v4i (&f)[N]) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) asm volatile("" : "+v"(f[i]));
+}
+
 template <int WB, int AB, int TC, int TT, int WAVES_C, int WAVES_T, int BK, int S, int OCC, int EPI>
 __global__ __launch_bounds__(WAVES_C *WAVES_T * 64, OCC)
 void gemm_kernel(GemmParams p) {
@@ -584,30 +597,42 @@ void gemm_kernel(GemmParams p) {
         x_kb[it] = chunk * 16;
     }
     const u32 lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem)) + (u32)wave * 1024u;
-    auto issue = [&](int kt) {
+    // The LOADS loads of a stage (weights first, then tokens) are issued in kParts groups: a burst of
+    // all of them from all four waves queues up in the CU's one address path and stalls every wave
+    // for hundreds of cycles, so the main loop spreads the groups over several MFMA steps.
+    constexpr int kParts = 3;
+    constexpr int kPartLoads = (LOADS + kParts - 1) / kParts;
+    auto issue_part = [&](int kt, auto PART) {
+        constexpr int lo = decltype(PART)::value * kPartLoads;
+        constexpr int hi = (lo + kPartLoads < LOADS) ? lo + kPartLoads : LOADS;
         const u32 dst = lds0 + (u32)(kt % S) * STAGE;
         if (ktail && kt == nk - 1) {
             // last stage of a K that does not fill it: chunks past the row end come from zeros
-#pragma unroll
-            for (int it = 0; it < W_ITERS; ++it) {
-                const uint8_t *src = wbase + (int64_t)kt * WROW + w_off[it];
-                if (kt * WROW + w_kb[it] >= p.kbytes_w16) src = reinterpret_cast<const uint8_t *>(g_zero16);
-                dma16_ptr(src, dst + it * (NT * 16));
-            }
-#pragma unroll
-            for (int it = 0; it < X_ITERS; ++it) {
-                const uint8_t *src = xbase + (int64_t)kt * XROW + x_off[it];
-                if (kt * XROW + x_kb[it] >= p.kbytes_x16) src = reinterpret_cast<const uint8_t *>(g_zero16);
-                dma16_ptr(src, dst + WBUF + it * (NT * 16));
-            }
+            static_for<(hi > lo ? hi - lo : 0)>([&](auto I) {
+                constexpr int l = lo + decltype(I)::value;
+                if constexpr (l < W_ITERS) {
+                    const uint8_t *src = wbase + (int64_t)kt * WROW + w_off[l];
+                    if (kt * WROW + w_kb[l] >= p.kbytes_w16) src = reinterpret_cast<const uint8_t *>(g_zero16);
+                    dma16_ptr(src, dst + l * (NT * 16));
+                } else {
+                    constexpr int it = l - W_ITERS;
+                    const uint8_t *src = xbase + (int64_t)kt * XROW + x_off[it];
+                    if (kt * XROW + x_kb[it] >= p.kbytes_x16) src = reinterpret_cast<const uint8_t *>(g_zero16);
+                    dma16_ptr(src, dst + WBUF + it * (NT * 16));
+                }
+            });
         } else {
             const uint8_t *wk = wbase + (int64_t)kt * WROW;
             const uint8_t *xk = xbase + (int64_t)kt * XROW;
-#pragma unroll
-            for (int it = 0; it < W_ITERS; ++it) dma16(w_off[it], wk, dst + it * (NT * 16));
-#pragma unroll
-            for (int it = 0; it < X_ITERS; ++it) dma16(x_off[it], xk, dst + WBUF + it * (NT * 16));
+            static_for<(hi > lo ? hi - lo : 0)>([&](auto I) {
+                constexpr int l = lo + decltype(I)::value;
+                if constexpr (l < W_ITERS) dma16(w_off[l], wk, dst + l * (NT * 16));
+                else dma16(x_off[l - W_ITERS], xk, dst + WBUF + (l - W_ITERS) * (NT * 16));
+            });
         }
+    };
+    auto issue = [&](int kt) {
+        static_for<kParts>([&](auto P) { issue_part(kt, P); });
     };
     // Integer-only epilogue: this lane's share of the tile's comparator references is requested
     // now, ahead of every operand load (loads retire in order, so the hand-counted waits of the
@@ -684,87 +709,174 @@ void gemm_kernel(GemmParams p) {
                 x_rd[ss][j] = (u32)(WBUF + (xrow * XCH + (((xbo >> 4) + j) ^ swz<XCH>(xrow))) * 16 + (xbo & 15));
         }
     }
-    auto compute = [&](int buf) {
+    // ---- main loop, software-pipelined by hand -------------------------------------------------
+    // A k-stage is NSS sub-steps of 64 values; a sub-step is two MFMA steps s = 0, 1 of 32 values.
+    // Per sub-step a lane fetches one packed piece per operand block ("raw": 32 values each) and
+    // unpacks half of it per MFMA step into int8 fragments ("frag").  Fragments are double
+    // buffered: while the NC*NTK MFMAs of one step run on one set, the VALU fills the other set,
+    // and the LDS reads of the next sub-step are issued as soon as the current raw registers have
+    // been unpacked, so their latency hides behind the MFMAs that follow.  The wait for the next
+    // k-stage, the workgroup barrier and the issue of the stage after it sit in the middle of the
+    // last sub-step (not between k-steps), where the matrix pipe still holds queued work.
+    constexpr int WRAW = (32 * WB) / 32, XRAW = (32 * AB) / 32;   // dwords of raw data per lane, block and sub-step
+    u32 wr[NC][WRAW], xr[NTK][XRAW];
+    v4i wf[2][NC], xf[2][NTK];
+    auto load_raw = [&](int buf, auto SS) {
+        constexpr int ss = decltype(SS)::value;
         const uint8_t *stage = smem + buf * STAGE;
 #pragma unroll
-        for (int ss = 0; ss < NSS; ++ss) {
-            // operands are fetched packed and unpacked one MFMA operand at a time
-            constexpr int WRAW = (32 * WB) / 32, XRAW = (32 * AB) / 32;   // dwords per lane
-            u32 wr[NC][WRAW], xr[NTK][XRAW];
-#pragma unroll
-            for (int ci = 0; ci < NC; ++ci) {
-                const uint8_t *src = stage + w_rd[ss][0] + ci * 32 * WROW;
-                if constexpr (WB == 4) {
-                    uint4 v = *reinterpret_cast<const uint4 *>(src);
-                    wr[ci][0] = v.x; wr[ci][1] = v.y; wr[ci][2] = v.z; wr[ci][3] = v.w;
-                } else if constexpr (WB == 2) {
-                    uint2 v = *reinterpret_cast<const uint2 *>(src);
-                    wr[ci][0] = v.x; wr[ci][1] = v.y;
-                } else {
-                    uint4 v0 = *reinterpret_cast<const uint4 *>(src);
-                    uint4 v1 = *reinterpret_cast<const uint4 *>(stage + w_rd[ss][WRD - 1] + ci * 32 * WROW);
-                    wr[ci][0] = v0.x; wr[ci][1] = v0.y; wr[ci][2] = v0.z; wr[ci][3] = v0.w;
-                    wr[ci][4] = v1.x; wr[ci][5] = v1.y; wr[ci][6] = v1.z; wr[ci][7] = v1.w;
-                }
+        for (int ci = 0; ci < NC; ++ci) {
+            const uint8_t *src = stage + w_rd[ss][0] + ci * 32 * WROW;
+            if constexpr (WB == 4) {
+                uint4 v = *reinterpret_cast<const uint4 *>(src);
+                wr[ci][0] = v.x; wr[ci][1] = v.y; wr[ci][2] = v.z; wr[ci][3] = v.w;
+            } else if constexpr (WB == 2) {
+                uint2 v = *reinterpret_cast<const uint2 *>(src);
+                wr[ci][0] = v.x; wr[ci][1] = v.y;
+            } else {
+                uint4 v0 = *reinterpret_cast<const uint4 *>(src);
+                uint4 v1 = *reinterpret_cast<const uint4 *>(stage + w_rd[ss][WRD - 1] + ci * 32 * WROW);
+                wr[ci][0] = v0.x; wr[ci][1] = v0.y; wr[ci][2] = v0.z; wr[ci][3] = v0.w;
+                wr[ci][4] = v1.x; wr[ci][5] = v1.y; wr[ci][6] = v1.z; wr[ci][7] = v1.w;
             }
+        }
 #pragma unroll
-            for (int ti = 0; ti < NTK; ++ti) {
-                const uint8_t *src = stage + x_rd[ss][0] + ti * 32 * XROW;
-                if constexpr (AB == 4) {
-                    uint4 v = *reinterpret_cast<const uint4 *>(src);
-                    xr[ti][0] = v.x; xr[ti][1] = v.y; xr[ti][2] = v.z; xr[ti][3] = v.w;
-                } else {
-                    uint4 v0 = *reinterpret_cast<const uint4 *>(src);
-                    uint4 v1 = *reinterpret_cast<const uint4 *>(stage + x_rd[ss][XRD - 1] + ti * 32 * XROW);
-                    xr[ti][0] = v0.x; xr[ti][1] = v0.y; xr[ti][2] = v0.z; xr[ti][3] = v0.w;
-                    xr[ti][4] = v1.x; xr[ti][5] = v1.y; xr[ti][6] = v1.z; xr[ti][7] = v1.w;
-                }
-            }
-#pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                v4i wf[NC], xf[NTK];
-#pragma unroll
-                for (int ci = 0; ci < NC; ++ci) {
-                    if constexpr (WB == 4) wf[ci] = unpack4_x16(wr[ci][2 * s], wr[ci][2 * s + 1]);
-                    else if constexpr (WB == 2) wf[ci] = unpack2_x64(wr[ci][s]);
-                    else { wf[ci][0] = (int)wr[ci][4 * s]; wf[ci][1] = (int)wr[ci][4 * s + 1];
-                           wf[ci][2] = (int)wr[ci][4 * s + 2]; wf[ci][3] = (int)wr[ci][4 * s + 3]; }
-                }
-#pragma unroll
-                for (int ti = 0; ti < NTK; ++ti) {
-                    if constexpr (AB == 4) {
-                        if constexpr (WB == 2) xf[ti] = unpack4_x16_order2(xr[ti][2 * s], xr[ti][2 * s + 1]);
-                        else xf[ti] = unpack4_x16(xr[ti][2 * s], xr[ti][2 * s + 1]);
-                    } else {
-                        xf[ti][0] = (int)xr[ti][4 * s]; xf[ti][1] = (int)xr[ti][4 * s + 1];
-                        xf[ti][2] = (int)xr[ti][4 * s + 2]; xf[ti][3] = (int)xr[ti][4 * s + 3];
-                    }
-                }
-#pragma unroll
-                for (int ci = 0; ci < NC; ++ci)
-#pragma unroll
-                    for (int ti = 0; ti < NTK; ++ti)
-                        if constexpr (SWAP)
-                            acc[ci][ti] = __builtin_amdgcn_mfma_i32_32x32x32_i8(xf[ti], wf[ci], acc[ci][ti], 0, 0, 0);
-                        else
-                            acc[ci][ti] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[ci], xf[ti], acc[ci][ti], 0, 0, 0);
+        for (int ti = 0; ti < NTK; ++ti) {
+            const uint8_t *src = stage + x_rd[ss][0] + ti * 32 * XROW;
+            if constexpr (AB == 4) {
+                uint4 v = *reinterpret_cast<const uint4 *>(src);
+                xr[ti][0] = v.x; xr[ti][1] = v.y; xr[ti][2] = v.z; xr[ti][3] = v.w;
+            } else {
+                uint4 v0 = *reinterpret_cast<const uint4 *>(src);
+                uint4 v1 = *reinterpret_cast<const uint4 *>(stage + x_rd[ss][XRD - 1] + ti * 32 * XROW);
+                xr[ti][0] = v0.x; xr[ti][1] = v0.y; xr[ti][2] = v0.z; xr[ti][3] = v0.w;
+                xr[ti][4] = v1.x; xr[ti][5] = v1.y; xr[ti][6] = v1.z; xr[ti][7] = v1.w;
             }
         }
     };
-
-    // Stage kt is complete once all but the loads of the (at most S-2) younger stages have
-    // retired; the barrier then also tells that every wave has finished reading stage kt-1, whose
-    // buffer the next issue overwrites.
-    for (int kt = 0; kt < nk; ++kt) {
-        const int younger = nk - 1 - kt;
+    // raw -> fragment set `fb` for MFMA step s of the current sub-step
+    auto unpack = [&](auto S_, auto FB) {
+        constexpr int s = decltype(S_)::value, fb = decltype(FB)::value;
+#pragma unroll
+        for (int ci = 0; ci < NC; ++ci) {
+            if constexpr (WB == 4) wf[fb][ci] = unpack4_x16(wr[ci][2 * s], wr[ci][2 * s + 1]);
+            else if constexpr (WB == 2) wf[fb][ci] = unpack2_x64(wr[ci][s]);
+            else { wf[fb][ci][0] = (int)wr[ci][4 * s]; wf[fb][ci][1] = (int)wr[ci][4 * s + 1];
+                   wf[fb][ci][2] = (int)wr[ci][4 * s + 2]; wf[fb][ci][3] = (int)wr[ci][4 * s + 3]; }
+        }
+#pragma unroll
+        for (int ti = 0; ti < NTK; ++ti) {
+            if constexpr (AB == 4) {
+                if constexpr (WB == 2) xf[fb][ti] = unpack4_x16_order2(xr[ti][2 * s], xr[ti][2 * s + 1]);
+                else xf[fb][ti] = unpack4_x16(xr[ti][2 * s], xr[ti][2 * s + 1]);
+            } else {
+                xf[fb][ti][0] = (int)xr[ti][4 * s]; xf[fb][ti][1] = (int)xr[ti][4 * s + 1];
+                xf[fb][ti][2] = (int)xr[ti][4 * s + 2]; xf[fb][ti][3] = (int)xr[ti][4 * s + 3];
+            }
+        }
+    };
+    auto mma = [&](auto FB) {
+        constexpr int fb = decltype(FB)::value;
+#pragma unroll
+        for (int ci = 0; ci < NC; ++ci)
+#pragma unroll
+            for (int ti = 0; ti < NTK; ++ti)
+                if constexpr (SWAP)
+                    acc[ci][ti] = __builtin_amdgcn_mfma_i32_32x32x32_i8(xf[fb][ti], wf[fb][ci], acc[ci][ti], 0, 0, 0);
+                else
+                    acc[ci][ti] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[fb][ci], xf[fb][ti], acc[ci][ti], 0, 0, 0);
+    };
+    // Interleave pattern of one MFMA step: NC*NTK matrix instructions with the unpack arithmetic of
+    // the next step spread evenly between them (then, where given, the LDS reads of the next sub-step).
+    constexpr int kMma = NC * NTK;
+    constexpr int kUnpackOps = (WB == 8 ? 0 : (WB == 4 ? 6 : 7) * NC) + (AB == 8 ? 0 : (WB == 2 ? 10 : 6) * NTK);
+    constexpr int kValuPerMma = (kUnpackOps + kMma - 1) / kMma;
+    constexpr int kRawReads = NC * WRD + NTK * XRD;
+    auto pattern = [&](bool reads_after) {
+#pragma unroll
+        for (int i = 0; i < kMma; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                 // one MFMA
+            if (kValuPerMma > 0) __builtin_amdgcn_sched_group_barrier(0x002, kValuPerMma, 0);   // its share of VALU
+        }
+        if (reads_after) __builtin_amdgcn_sched_group_barrier(0x100, kRawReads, 0);              // DS reads
+    };
+    // Stage j is complete once all but the loads of the (at most S-2) younger stages have retired;
+    // the barrier then also tells that every wave has finished reading stage j-1, whose buffer the
+    // next issue overwrites.
+    auto sync_stage = [&](int j) {
+        const int younger = nk - 1 - j;
         if (younger >= S - 2) wait_vmcnt<(S - 2) * LOADS>();
         else if (younger == 1) wait_vmcnt<LOADS>();
         else wait_vmcnt<0>();
         __syncthreads();
-        if (kt + S - 1 < nk) issue(kt + S - 1);
-        compute(kt % S);
-    }
+        if (j + S - 1 < nk) {
+            if (j == 0) issue(j + S - 1);
+            else issue_part(j + S - 1, std::integral_constant<int, 0>{});
+        }
+    };
+    // The fragments of a set are made "used" at the end of the step that fills them, so the
+    // compiler cannot sink their arithmetic past the branches of the synchronisation code (where
+    // it would no longer overlap with any MFMA).
+    auto pin = [&](auto FB) {
+        constexpr int fb = decltype(FB)::value;
+        pin_frags(wf[fb]);
+        pin_frags(xf[fb]);
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    sync_stage(0);
+    load_raw(0, I0{});
+    unpack(I0{}, I0{});
+    // One k-stage.  NEXT: another stage follows (its synchronisation, the issue of a later stage and
+    // the first raw reads of the next stage are part of this one); the last stage is a separate
+    // instantiation, so that neither copy carries a branch between an MFMA step and its unpacking.
+    auto kstep = [&](int kt, auto NEXT_) {
+        constexpr bool NEXT = decltype(NEXT_)::value;
+        const int buf = kt % S;
+        static_for<NSS>([&](auto SS) {
+            constexpr int ss = decltype(SS)::value;
+            constexpr bool last_ss = (ss + 1 == NSS);
+            // the rest of the stage whose first loads followed the previous synchronisation
+            if constexpr (ss == 0) {
+                if (kt >= 1 && kt + S - 1 < nk) issue_part(kt + S - 1, I1{});
+            }
+            // step s = 0 runs; step s = 1 is unpacked; then the raw registers are free
+            __builtin_amdgcn_sched_barrier(0);
+            mma(I0{});
+            unpack(I1{}, I1{});
+            if constexpr (!last_ss) {
+                load_raw(buf, std::integral_constant<int, (last_ss ? 0 : ss + 1)>{});
+                pattern(true);
+                pin(I1{});
+                __builtin_amdgcn_sched_barrier(0);
+            } else {
+                pattern(false);
+                pin(I1{});
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (NEXT) {
+                    sync_stage(kt + 1);
+                    load_raw((kt + 1) % S, I0{});
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            if constexpr (ss == 0) {
+                if (kt >= 1 && kt + S - 1 < nk) issue_part(kt + S - 1, std::integral_constant<int, 2>{});
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // step s = 1 runs; step s = 0 of the next sub-step is unpacked
+            mma(I1{});
+            if constexpr (!last_ss || NEXT) {
+                unpack(I0{}, I0{});
+                pattern(false);
+                pin(I0{});
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+    for (int kt = 0; kt < nk - 1; ++kt) kstep(kt, std::true_type{});
+    kstep(nk - 1, std::false_type{});
     __syncthreads();
+
 
     // ---- epilogue -------------------------------------------------------------------------
     constexpr int shift = Shift<WB, AB>::value;
@@ -808,20 +920,25 @@ void gemm_kernel(GemmParams p) {
             // Q and K tiles: per-head LayerNorm quantizer; V tiles fall through to the plain one
             const int cbw = c0 + wave_c * WC;                       // the wave's head starts here
             if (cbw < 2 * p.D) {
-                static_assert(EPI != kEpiHeadNorm || (NC == 2 && NTK == 2 && WC == 64), "one head per wave");
+                static_assert(EPI != kEpiHeadNorm || (NC == 2 && NTK % 2 == 0 && WC == 64), "one head per wave");
                 int which;
                 const int64_t ch_part = packed_channel_part(p, cbw, which);
-                const int64_t tk = packed_token_part(p, t0 + wave_t * WT + 32 * g + li);
-                uint8_t *dst = (ch_part >= 0 && tk >= 0) ? p.yq + tk + ch_part : nullptr;
                 const float step = which == 0 ? p.s_y[0] : p.s_y[1];
                 // folded scales unless folding was inexact somewhere in the tile: then the plain
                 // ones (kept behind the flag word) and the explicit shift
                 const float *sc64 = (fold_ok ? s_scs : s_raw) + wave_c * WC;
                 const int sh = fold_ok ? 0 : shift;
-                if (p.yq_sb == 4)
-                    epilogue_headnorm<4>(p, acc, sh, dst, sc64, s_bs + wave_c * WC, step, s_hg + wave_c * WC, s_hb + wave_c * WC);
-                else
-                    epilogue_headnorm<8>(p, acc, sh, dst, sc64, s_bs + wave_c * WC, step, s_hg + wave_c * WC, s_hb + wave_c * WC);
+                if constexpr (EPI == kEpiHeadNorm) {
+                    static_for<NTK / 2>([&](auto PI) {
+                        constexpr int pair = decltype(PI)::value;
+                        const int64_t tk = packed_token_part(p, t0 + wave_t * WT + 64 * pair + 32 * g + li);
+                        uint8_t *dst = (ch_part >= 0 && tk >= 0) ? p.yq + tk + ch_part : nullptr;
+                        if (p.yq_sb == 4)
+                            epilogue_headnorm<4, NTK, pair>(p, acc, sh, dst, sc64, s_bs + wave_c * WC, step, s_hg + wave_c * WC, s_hb + wave_c * WC);
+                        else
+                            epilogue_headnorm<8, NTK, pair>(p, acc, sh, dst, sc64, s_bs + wave_c * WC, step, s_hg + wave_c * WC, s_hb + wave_c * WC);
+                    });
+                }
                 return;
             }
         }
@@ -979,8 +1096,8 @@ hipError_t gemm_launch(GemmParams p, int wb, int ab, hipStream_t stream) {
                 epi = (epi == kEpiF32) ? epi : kEpiGeneric;
             }
     }
-    if (wb == 4 && ab == 4) return launch_epi<4, 4, 128, 128, 2, 2, 128, 3, 3>(p, epi, stream);
-    if (wb == 2 && ab == 4) return launch_epi<2, 4, 128, 128, 2, 2, 128, 3, 3>(p, epi, stream);
+    if (wb == 4 && ab == 4) return launch_epi<4, 4, VITQ_TC, VITQ_TT, 2, 2, 128, VITQ_S44, VITQ_OCC44>(p, epi, stream);
+    if (wb == 2 && ab == 4) return launch_epi<2, 4, VITQ_TC, VITQ_TT, 2, 2, 128, VITQ_S44, VITQ_OCC44>(p, epi, stream);
     if (wb == 8 && ab == 8) return launch_epi<8, 8, 128, 128, 2, 2, VITQ_BK88, VITQ_S88, VITQ_OCC88>(p, epi, stream);
     if (wb == 8 && ab == 4) return launch_epi<8, 4, 128, 128, 2, 2, VITQ_BK84, VITQ_S84, VITQ_OCC84>(p, epi, stream);
     return hipErrorInvalidValue;
