@@ -30,8 +30,11 @@ namespace {
 #ifndef VITQ_TC
 #define VITQ_TC 128
 #define VITQ_TT 256
+#define VITQ_WC 2
+#define VITQ_WT 4
+#define VITQ_BK44 128
 #define VITQ_S44 3
-#define VITQ_OCC44 2
+#define VITQ_OCC44 4
 #endif
 #ifndef VITQ_BK88
 #define VITQ_BK88 64
@@ -41,7 +44,7 @@ namespace {
 #ifndef VITQ_BK84
 #define VITQ_BK84 128
 #define VITQ_S84 2
-#define VITQ_OCC84 3
+#define VITQ_OCC84 4
 #endif
 enum Epi { kEpiGeneric = 0, kEpiF32 = 1, kEpiQuant = 2, kEpiQuantGelu = 3, kEpiHeadNorm = 4, kEpiAbsorbed = 5, kEpiAbsorbedBig = 6 };   // Big: more than 15 references per channel
 
@@ -221,10 +224,16 @@ __device__ __forceinline__ void pack_store16(const GemmParams &p, uint8_t *dst, 
         }
         // stored levels are biased by -qmin = 2^(bits-1); remove it per nibble, modulo 16 and
         // without borrows across nibbles (for 4-bit levels this is a flip of bit 3)
-        const u32 fix = 0x11111111u * ((u32)bias8 & 0xFu);
         const u32 a0 = ev0 | (od0 << 4), a1 = ev1 | (od1 << 4);
-        const u32 w0 = ((a0 | 0x88888888u) - (fix & 0x77777777u)) ^ ((a0 ^ ~fix) & 0x88888888u);
-        const u32 w1 = ((a1 | 0x88888888u) - (fix & 0x77777777u)) ^ ((a1 ^ ~fix) & 0x88888888u);
+        u32 w0, w1;
+        if (bias8 == 8.0f) {                 // (uniform) 4-bit levels: subtracting 8 modulo 16 flips bit 3
+            w0 = a0 ^ 0x88888888u;
+            w1 = a1 ^ 0x88888888u;
+        } else {
+            const u32 fix = 0x11111111u * ((u32)bias8 & 0xFu);
+            w0 = ((a0 | 0x88888888u) - (fix & 0x77777777u)) ^ ((a0 ^ ~fix) & 0x88888888u);
+            w1 = ((a1 | 0x88888888u) - (fix & 0x77777777u)) ^ ((a1 ^ ~fix) & 0x88888888u);
+        }
         *reinterpret_cast<uint2 *>(dst) = make_uint2(w0, w1);
     } else {
         // 8-bit storage: the bias -qmin = 2^(bits-1) is removed modulo 256
@@ -242,6 +251,36 @@ __device__ __forceinline__ void pack_store16(const GemmParams &p, uint8_t *dst, 
     }
 }
 
+// Eight levels (floats holding level - qmin) -> one word of 4-bit fields (w[0]) or two words of
+// 8-bit fields, two's complement, bias removed.
+__device__ __forceinline__ void pack8(const GemmParams &p, const float (&lv)[8], float bias8, u32 (&w)[2]) {
+    if (p.yq_sb == 4) {
+        u32 ev = 0, od = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            ev = __builtin_amdgcn_cvt_pk_u8_f32(lv[2 * i], i, ev);
+            od = __builtin_amdgcn_cvt_pk_u8_f32(lv[2 * i + 1], i, od);
+        }
+        const u32 a = ev | (od << 4);
+        if (bias8 == 8.0f) {                 // (uniform) 4-bit levels: subtracting 8 modulo 16 flips bit 3
+            w[0] = a ^ 0x88888888u;
+        } else {
+            const u32 fix = 0x11111111u * ((u32)bias8 & 0xFu);
+            w[0] = ((a | 0x88888888u) - (fix & 0x77777777u)) ^ ((a ^ ~fix) & 0x88888888u);
+        }
+        w[1] = 0;
+    } else {
+        const u32 fix = 0x01010101u * ((u32)bias8 & 0xFFu);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            u32 v = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v = __builtin_amdgcn_cvt_pk_u8_f32(lv[4 * j + i], i, v);
+            w[j] = ((v | 0x80808080u) - (fix & 0x7F7F7F7Fu)) ^ ((v ^ ~fix) & 0x80808080u);
+        }
+    }
+}
+
 // A 16-channel group that lies wholly beyond the last output channel but inside the 16-byte
 // padded row: the packed format wants zero bytes there.
 __device__ __forceinline__ void store_zero_group(const GemmParams &p, uint8_t *dst) {
@@ -251,67 +290,96 @@ __device__ __forceinline__ void store_zero_group(const GemmParams &p, uint8_t *d
 }
 
 // ---- guarded fast requantization (Nout % 16 == 0; 4- or 8-bit storage) ------------------------
-// Cheap value: t8 = fma(y, 1/s, -qmin) ~ y/s - qmin, level+(-qmin) = rint(t8).  With T = y/s:
-//   |t8 + qmin - fl(T)| <= |T| * 2^-23 + ulp(t8)/2  <  eps0 = 2^(bits-22)   whenever |T| <= qmax+2,
-// and beyond that range both values clamp to the same level.  If rint(t8) is not within
-// 1/2 - eps0 of t8, the definition rounds to the same integer; otherwise the element is redone
-// exactly.  For GELU the cheap activation (hardware exp2 / rcp) is within
-// 2^-18 * |y| * max(1,|y|) of the definition's, which widens the guard per element.
+// Definition: level = clamp(rint(T)), T = RN(y / s).  Cheap value: with r = RN(1/s), g = eps0 =
+// 2^(bits-22) and C = -qmin + 1/2 - g (exactly representable),
+//     u = fma(y, r, C),   |u - (T - qmin + 1/2 - g)| <= |T| * 2^-23 + ulp(u)/2  <  g   for |T| <= qmax + 2.
+// If fract(u) < 1 - 2g then T - qmin + 1/2 lies strictly inside (floor(u), floor(u) + 1): it is not
+// a tie and rint(T) - qmin = floor(u) = u - fract(u) (an exact subtraction).  Otherwise the element
+// sits within the error bound of a rounding boundary and is redone with the definition's own
+// operations.  Beyond |T| = qmax + 2 both clamp to the same level; a NaN or infinity gives a NaN
+// fraction, whose bit pattern compares above every threshold, so it is redone too.
+// With GELU the cheap activation (hardware exp2 / rcp) is within 2^-18 * |y| * max(1,|y|) of the
+// definition's, which widens the guard per element (there the test is on |t - rint(t)|).
+// The sixteen channels of a lane are done in two halves of eight (each with its own test and, if
+// need be, its own exact redo): the working set stays small enough for four waves per SIMD.
+// lscs / lbs: this lane's sixteen folded scales and biases in LDS.
 template <bool GELU>
 __device__ __forceinline__ void epilogue_quant(const GemmParams &p, const v16i &acc, int shift, uint8_t *dst,
-                                               float s_y, float r_y, int cb, const float (&scs)[16],
-                                               const float (&bs)[16], bool force_exact) {
+                                               float s_y, float r_y, int cb, const float *lscs, const float *lbs,
+                                               bool force_exact) {
     if (!dst) return;
     const float bias8 = -p.qminf;
     const float top = p.qmaxf - p.qminf;
-    const float thr0 = 0.5f - p.eps0;
-    const float gguard = p.gelu_guard * r_y;
-    float lv[16];
-    // worst = max over the elements of (distance to the nearest integer + that element's guard),
-    // taken on the bit patterns: the values are >= +0, where unsigned order is float order and
-    // a NaN compares above everything (so it is caught, which a float max would drop)
-    u32 worst = force_exact ? 0x7F800000u : 0u;
-    float dist[16];
+    u32 words[4];
+    static_for<2>([&](auto H) {
+        constexpr int h = decltype(H)::value;
+        float scs[8], bs[8];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const float y = fmaf((float)acc[r], scs[r], bs[r]);        // the definition's y, exactly
-        float g = y;
-        float t8, q8;
+        for (int j = 0; j < 2; ++j) {
+            const float4 a = *reinterpret_cast<const float4 *>(lscs + 8 * h + 4 * j);
+            const float4 b = *reinterpret_cast<const float4 *>(lbs + 8 * h + 4 * j);
+            scs[4 * j] = a.x; scs[4 * j + 1] = a.y; scs[4 * j + 2] = a.z; scs[4 * j + 3] = a.w;
+            bs[4 * j] = b.x; bs[4 * j + 1] = b.y; bs[4 * j + 2] = b.z; bs[4 * j + 3] = b.w;
+        }
+        float lv[8];
+        // worst = max over the elements of a non-negative per-element figure, taken on the bit
+        // patterns: there unsigned order is float order and a NaN compares above everything (so
+        // it is caught, which a float max would drop)
+        u32 worst = force_exact ? 0x7F800000u : 0u;
+        u32 fig[8];
+        u32 limit;
         if constexpr (GELU) {
-            // 0.5*y*(1+tanh(u)) = y - y/(1 + 2^(2u*log2 e)),  2u*log2e = y*(k0 + k1*y^2)
-            const float y2 = y * y;
-            const float w = fmaf(y2, 0x1.a5a7d0p-4f, 0x1.26aec2p+1f);
-            const float X = __builtin_amdgcn_exp2f(w * y);
-            const float rc = __builtin_amdgcn_rcpf(1.0f + X);
-            g = fmaf(-y, rc, y);
-            t8 = fmaf(g, r_y, bias8);
-            q8 = rintf(t8);
-            dist[r] = fmaf(fabsf(y) + y2, gguard, fabsf(t8 - q8));   // |y| + y^2 >= |y| * max(1, |y|)
+            const float gguard = p.gelu_guard * r_y;
+            limit = __float_as_uint(0.5f - p.eps0);
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                const float y = fmaf((float)acc[8 * h + r], scs[r], bs[r]);        // the definition's y, exactly
+                // 0.5*y*(1+tanh(u)) = y - y/(1 + 2^(2u*log2 e)),  2u*log2e = y*(k0 + k1*y^2)
+                const float y2 = y * y;
+                const float w = fmaf(y2, 0x1.a5a7d0p-4f, 0x1.26aec2p+1f);
+                const float X = __builtin_amdgcn_exp2f(w * y);
+                const float rc = __builtin_amdgcn_rcpf(1.0f + X);
+                const float g = fmaf(-y, rc, y);
+                const float t8 = fmaf(g, r_y, bias8);
+                const float q8 = rintf(t8);
+                fig[r] = __float_as_uint(fmaf(fabsf(y) + y2, gguard, fabsf(t8 - q8)));   // |y| + y^2 >= |y| * max(1, |y|)
+                lv[r] = __builtin_amdgcn_fmed3f(q8, 0.0f, top);
+            }
         } else {
-            t8 = fmaf(g, r_y, bias8);
-            q8 = rintf(t8);
-            dist[r] = fabsf(t8 - q8);
-        }
-        lv[r] = __builtin_amdgcn_fmed3f(q8, 0.0f, top);
-    }
+            const float C = (bias8 + 0.5f) - p.eps0;
+            limit = __float_as_uint(1.0f - 2.0f * p.eps0) - 1u;              // risky: fract(u) >= 1 - 2g
 #pragma unroll
-    for (int r = 0; r < 16; r += 2)
-        worst = max(worst, max(__float_as_uint(dist[r]), __float_as_uint(dist[r + 1])));
-    const bool risky = worst > __float_as_uint(thr0);
-    if (__builtin_amdgcn_ballot_w64(risky) != 0) {
-        // some element of this wave's 32x32 block sits within the error bound of a rounding
-        // boundary: redo the block with the definition's exact operation sequence (rare)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            // (re-read the channel's step: the folded copy may be inexact when force_exact is set)
-            const float sc = p.s_x * p.s_w[p.s_w_per_channel ? cb + r : 0];
-            float ye = fmaf((float)(acc[r] >> shift), sc, bs[r]);
-            if constexpr (GELU) ye = gelu_tanh(ye);
-            const float te = rintf(ye / s_y) + bias8;
-            lv[r] = __builtin_amdgcn_fmed3f(te, 0.0f, top);
+            for (int r = 0; r < 8; ++r) {
+                const float y = fmaf((float)acc[8 * h + r], scs[r], bs[r]);        // the definition's y, exactly
+                const float u = fmaf(y, r_y, C);
+                const float z = __builtin_amdgcn_fractf(u);
+                fig[r] = __float_as_uint(z);
+                lv[r] = __builtin_amdgcn_fmed3f(u - z, 0.0f, top);
+            }
         }
-    }
-    pack_store16(p, dst, lv, bias8);
+#pragma unroll
+        for (int r = 0; r < 8; r += 2) worst = max(worst, max(fig[r], fig[r + 1]));
+        const bool risky = worst > limit;
+        if (__builtin_amdgcn_ballot_w64(risky) != 0) {
+            // some element of these eight channels x 32 tokens sits within the error bound of a rounding
+            // boundary: redo them with the definition's exact operation sequence (rare)
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                // (re-read the channel's step: the folded copy may be inexact when force_exact is set)
+                const float sc = p.s_x * p.s_w[p.s_w_per_channel ? cb + 8 * h + r : 0];
+                float ye = fmaf((float)(acc[8 * h + r] >> shift), sc, bs[r]);
+                if constexpr (GELU) ye = gelu_tanh(ye);
+                const float te = rintf(ye / s_y) + bias8;
+                lv[r] = __builtin_amdgcn_fmed3f(te, 0.0f, top);
+            }
+        }
+        u32 w2[2];
+        pack8(p, lv, bias8, w2);
+        words[2 * h] = w2[0];
+        words[2 * h + 1] = w2[1];
+    });
+    if (p.yq_sb == 4) *reinterpret_cast<uint2 *>(dst) = make_uint2(words[0], words[2]);
+    else *reinterpret_cast<uint4 *>(dst) = make_uint4(words[0], words[1], words[2], words[3]);
 }
 
 // ---- per-head LayerNorm quantizers of Q and K in the QKV epilogue (Sec. IV-C, Table I) ----------
@@ -780,11 +848,12 @@ void gemm_kernel(GemmParams p) {
 #pragma unroll
         for (int ci = 0; ci < NC; ++ci)
 #pragma unroll
-            for (int ti = 0; ti < NTK; ++ti)
+            for (int ti = 0; ti < NTK; ++ti) {
                 if constexpr (SWAP)
                     acc[ci][ti] = __builtin_amdgcn_mfma_i32_32x32x32_i8(xf[fb][ti], wf[fb][ci], acc[ci][ti], 0, 0, 0);
                 else
                     acc[ci][ti] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[fb][ci], xf[fb][ti], acc[ci][ti], 0, 0, 0);
+            }
     };
     // Interleave pattern of one MFMA step: NC*NTK matrix instructions with the unpack arithmetic of
     // the next step spread evenly between them (then, where given, the LDS reads of the next sub-step).
@@ -989,17 +1058,9 @@ void gemm_kernel(GemmParams p) {
             constexpr int ci = decltype(CI)::value;
             const int cl = wave_c * WC + ci * 32 + 16 * g;     // channel offset inside the tile
             const int cb = c0 + cl;
-            float bs[16], scs[16];
             int64_t ch_part = -1;
             float s_y = 1.0f, r_y = 1.0f;
             if constexpr (EPI != kEpiGeneric) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float4 a = *reinterpret_cast<const float4 *>(s_scs + cl + 4 * j);
-                    const float4 b = *reinterpret_cast<const float4 *>(s_bs + cl + 4 * j);
-                    scs[4 * j] = a.x; scs[4 * j + 1] = a.y; scs[4 * j + 2] = a.z; scs[4 * j + 3] = a.w;
-                    bs[4 * j] = b.x; bs[4 * j + 1] = b.y; bs[4 * j + 2] = b.z; bs[4 * j + 3] = b.w;
-                }
                 int which;
                 ch_part = packed_channel_part(p, cb, which);
                 const float sy0 = p.s_y[0], sy1 = p.s_y[1], sy2 = p.s_y[2];
@@ -1012,7 +1073,7 @@ void gemm_kernel(GemmParams p) {
                 if constexpr (QUANT) {
                     uint8_t *dst = (ch_part >= 0 && tok_part[ti] >= 0) ? p.yq + tok_part[ti] + ch_part : nullptr;
                     if (cb >= p.Nout) store_zero_group(p, dst);
-                    else epilogue_quant<EPI == kEpiQuantGelu>(p, acc[ci][ti], shift, dst, s_y, r_y, cb, scs, bs, !fold_ok);
+                    else epilogue_quant<EPI == kEpiQuantGelu>(p, acc[ci][ti], shift, dst, s_y, r_y, cb, s_scs + cl, s_bs + cl, !fold_ok);
                 } else {
                     const int m = t0 + wave_t * WT + ti * 32 + li;
                     epilogue_generic(p, acc[ci][ti], shift, m, cb);
@@ -1046,7 +1107,13 @@ hipError_t launch_epi(const GemmParams &p, int epi, hipStream_t stream) {
         case kEpiF32: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, S, OCC, kEpiF32>(p, stream);
         case kEpiQuant: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, S, OCC, kEpiQuant>(p, stream);
         case kEpiQuantGelu: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, S, OCC, kEpiQuantGelu>(p, stream);
-        case kEpiHeadNorm: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, S, OCC, kEpiHeadNorm>(p, stream);
+        case kEpiHeadNorm: {
+            // this epilogue keeps a token's whole 64-channel head in registers on top of the
+            // accumulators: it runs with two waves per SIMD (256 registers) on 64x128 wave tiles
+            constexpr int stage = 128 * BK * WB / 8 + 256 * BK * AB / 8;
+            constexpr int S_HN = (3 * stage <= 80 * 1024) ? 3 : 2;
+            return launch<WB, AB, 128, 256, 2, 2, BK, S_HN, 2, kEpiHeadNorm>(p, stream);
+        }
         case kEpiAbsorbed: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, S, OCC, kEpiAbsorbed>(p, stream);
         case kEpiAbsorbedBig: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, S, OCC, kEpiAbsorbedBig>(p, stream);
         default: return launch<WB, AB, TC, TT, WAVES_C, WAVES_T, BK, S, OCC, kEpiGeneric>(p, stream);
@@ -1096,10 +1163,10 @@ hipError_t gemm_launch(GemmParams p, int wb, int ab, hipStream_t stream) {
                 epi = (epi == kEpiF32) ? epi : kEpiGeneric;
             }
     }
-    if (wb == 4 && ab == 4) return launch_epi<4, 4, VITQ_TC, VITQ_TT, 2, 2, 128, VITQ_S44, VITQ_OCC44>(p, epi, stream);
-    if (wb == 2 && ab == 4) return launch_epi<2, 4, VITQ_TC, VITQ_TT, 2, 2, 128, VITQ_S44, VITQ_OCC44>(p, epi, stream);
+    if (wb == 4 && ab == 4) return launch_epi<4, 4, VITQ_TC, VITQ_TT, VITQ_WC, VITQ_WT, VITQ_BK44, VITQ_S44, VITQ_OCC44>(p, epi, stream);
+    if (wb == 2 && ab == 4) return launch_epi<2, 4, 128, 128, 2, 2, 128, 2, 4>(p, epi, stream);
     if (wb == 8 && ab == 8) return launch_epi<8, 8, 128, 128, 2, 2, VITQ_BK88, VITQ_S88, VITQ_OCC88>(p, epi, stream);
-    if (wb == 8 && ab == 4) return launch_epi<8, 4, 128, 128, 2, 2, VITQ_BK84, VITQ_S84, VITQ_OCC84>(p, epi, stream);
+    if (wb == 8 && ab == 4) return launch_epi<8, 4, VITQ_TC, VITQ_TT, VITQ_WC, VITQ_WT, VITQ_BK84, VITQ_S84, VITQ_OCC84>(p, epi, stream);
     return hipErrorInvalidValue;
 }
 
