@@ -53,14 +53,16 @@ class Hip:
 
 
 def cpu_baseline(name, sharp, bits_w, bits_a, ops_per_image):
-    """The CPU oracle, as it stands, on a bounded sample of the same workload."""
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: once on all host
+    threads the box grants (OpenMP over images) and once on a single thread."""
     import numpy as np
     from oracle import vqo
     from paper_2504_18547_amd import workloads as wl
     threads = min(vqo.num_threads(), 16)
     dims = wl.block_dims(name)
     # sized for roughly 10-15 s of CPU work: 24 ViT-B blocks per thread, fewer of a larger block
-    n_img = threads * int(min(64, max(2, round(24 * 2.9e9 / ops_per_image))))
+    per_thread = int(min(64, max(2, round(24 * 2.9e9 / ops_per_image))))
+    n_img = threads * per_thread
     st = wl.block_steps(name, sharp, bits_w, bits_a)
     w_fp = wl.block_weights(name, sharp=sharp)
     wts = {}
@@ -69,15 +71,23 @@ def cpu_baseline(name, sharp, bits_w, bits_a, ops_per_image):
             s = vqo.weight_steps(w_fp["w_" + nm], bits_w)
             wts["w_" + nm] = vqo.quantize(w_fp["w_" + nm], s, bits_w, per_row=True)
             wts["sw_" + nm], wts["b_" + nm] = s, w_fp["b_" + nm]
-    tokens = wl.block_tokens(name, list(range(n_img))).reshape(n_img * dims["N"], dims["D"])
-    t0 = time.perf_counter()
-    xq = vqo.quantize(tokens, st["s_x"], bits_a)
-    vqo.attention_block(xq, n_img, dims, wts, st, bits_a=bits_a, bits_p=bits_a, dumps=False, threads=threads)
-    dt = time.perf_counter() - t0
-    ips = n_img / dt
+
+    def leg(images, nthreads):
+        tokens = wl.block_tokens(name, list(range(images))).reshape(images * dims["N"], dims["D"])
+        t0 = time.perf_counter()
+        xq = vqo.quantize(tokens, st["s_x"], bits_a)
+        vqo.attention_block(xq, images, dims, wts, st, bits_a=bits_a, bits_p=bits_a, dumps=False, threads=nthreads)
+        return time.perf_counter() - t0
+
+    dt = leg(n_img, threads)
+    n1 = max(2, per_thread // 4)
+    dt1 = leg(n1, 1)
+    ips, ips1 = n_img / dt, n1 / dt1
     return {"value": ips * ops_per_image / 1e12, "unit": "TOPS", "images_per_s": ips, "cores": threads,
             "kind": "oracle", "seconds": dt,
-            "sample": "%d images of %s through oracle/vqo.c (quantize + whole block), OpenMP over images" % (n_img, name)}
+            "sample": "%d images of %s through oracle/vqo.c (quantize + whole block), OpenMP over images" % (n_img, name),
+            "one_core": {"value": ips1 * ops_per_image / 1e12, "unit": "TOPS", "images_per_s": ips1, "cores": 1,
+                         "seconds": dt1, "sample": "%d images, one thread" % n1}}
 
 
 def main():
@@ -96,6 +106,8 @@ def main():
     ap.add_argument("--prepack", action="store_true",
                     help="give the block the expanded int8 weight copies made once by vq_prepack_weight "
                          "instead of letting every GEMM tile unpack the packed weights itself")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="time eager launches instead of replays of the step captured into one HIP graph")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three 1 GiB device-to-device copies before the steps (a kernel of known "
                          "traffic, used to scale the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -144,20 +156,36 @@ def main():
     ws = torch.empty(vitq.vq_attention_block_workspace(desc, B), dtype=torch.uint8, device="cuda")
 
     hip = Hip()
-    stream = torch.cuda.current_stream().cuda_stream
     n_ev = 6 if hidden else 4
     K, W = args.steps, args.warmup
-    ev_q = [hip.event() for _ in range(K)]
-    ev_sets = [(C.c_void_p * n_ev)(*[hip.event() for _ in range(n_ev)]) for _ in range(K)]
 
-    def step(i=None):
-        if i is not None:
-            hip.record(ev_q[i], stream)
-            desc.stage_events = C.cast(ev_sets[i], C.POINTER(C.c_void_p))
-        else:
-            desc.stage_events = None
-        vitq.vq_quantize(tokens, st["s_x"], None, xq)
-        vitq.vq_attention_block(desc, xq, B, y, ws)
+    def make_step(desc_, tokens_, xq_, y_, ws_, sx):
+        def step():
+            vitq.vq_quantize(tokens_, sx, None, xq_)
+            vitq.vq_attention_block(desc_, xq_, B, y_, ws_)
+        return step
+
+    def timed(step_fn, use_graph):
+        """W untimed + K timed passes of step_fn; returns seconds per step.  With use_graph the step is
+        captured once into a HIP graph (after eager warm-up, so that nothing but kernel launches is
+        recorded) and the timed region replays it."""
+        for _ in range(max(W, 2)):
+            step_fn()
+        torch.cuda.synchronize()
+        run = step_fn
+        if use_graph:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                step_fn()
+            run = g.replay
+            for _ in range(2):
+                run()
+            torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(K):
+            run()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / K
 
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
@@ -166,16 +194,23 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    for _ in range(W):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(K):
-        step(i)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    desc.stage_events = None
+    step = make_step(desc, tokens, xq, y, ws, st["s_x"])
+    use_graph = not args.no_graph
+    sec_per_step = timed(step, use_graph)
+    dt = sec_per_step * K
 
-    # ---- per-stage durations from the events recorded inside the timed region ------------------
+    # ---- per-stage durations: a separate eager pass of the same K steps with HIP events recorded on
+    # the launch stream between the stages (kept out of the timed region: the records cost time) ----
+    stream = torch.cuda.current_stream().cuda_stream
+    ev_q = [hip.event() for _ in range(K)]
+    ev_sets = [(C.c_void_p * n_ev)(*[hip.event() for _ in range(n_ev)]) for _ in range(K)]
+    for i in range(K):
+        hip.record(ev_q[i], stream)
+        desc.stage_events = C.cast(ev_sets[i], C.POINTER(C.c_void_p))
+        step()
+    desc.stage_events = None
+    torch.cuda.synchronize()
     stage_ms = {"quantize": 0.0}
     for nm in STAGES[:n_ev - 1]:
         stage_ms[nm] = 0.0
@@ -185,6 +220,15 @@ def main():
         for j, nm in enumerate(STAGES[:n_ev - 1]):
             stage_ms[nm] += hip.elapsed_ms(evs[j], evs[j + 1])
     stage_ms = {k: v / K for k, v in stage_ms.items()}
+
+    # ---- what the matrix cores of this machine sustain (register-resident MFMA loop, no memory) ----
+    e0, e1 = hip.event(), hip.event()
+    vitq.vq_probe_mfma_i8(2000)
+    hip.record(e0, stream)
+    probe_ops = vitq.vq_probe_mfma_i8(20000)
+    hip.record(e1, stream)
+    torch.cuda.synchronize()
+    peak_measured = probe_ops / (hip.elapsed_ms(e0, e1) * 1e-3) / 1e12
 
     macs = opcount.block_macs(D, H, N, hidden)
     ops_img = 2 * sum(macs.values())
@@ -202,14 +246,23 @@ def main():
     traffic, traffic_detail = None, None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath) and not args.prepack:
+        import hashlib
+        with open(os.path.join(ROOT, "paper_2504_18547_amd", "csrc", "gemm.hip"), "rb") as f:
+            gemm_sha = hashlib.sha1(f.read()).hexdigest()
         with open(tpath) as f:
             traffic_detail = json.load(f).get("%s/w%da%d/b%d" % (name, bw, ba, B))
-        if traffic_detail:
+        # counters of an older kernel say nothing about this one: null unless they were taken on this source
+        if traffic_detail and traffic_detail.get("gemm_source_sha1") == gemm_sha:
             traffic = traffic_detail["bytes_per_launch"]
+        elif traffic_detail:
+            traffic_detail = dict(traffic_detail, stale="csrc/gemm.hip changed since these counters were taken")
     roofline = {"kernel": "gemm_kernel<W%d,A%d> (4 launches per step: qkv, proj, fc1, fc2)" % (bw, sa),
                 "bound": "mfma", "achieved": achieved, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                 "frac": achieved / INT8_MFMA_PEAK_TOPS,
+                "peak_measured": peak_measured, "frac_of_measured": achieved / peak_measured,
                 "avg_launch_ms": gemm_ms / len(lin), "ops_per_launch": gemm_ops / len(lin),
+                "durations": "HIP events between the stages on the launch stream, in a separate eager pass of the "
+                             "same %d steps right after the timed region" % K,
                 "traffic": traffic, "traffic_detail": traffic_detail}
     by = opcount.block_algorithmic_bytes(D, H, N, hidden, sa, 4 if bw == 3 else bw)
     alg_bytes = B * (by["per_image"] + N * D * 4) + by["weights"]     # + fp32 tokens read by vq_quantize
@@ -224,16 +277,40 @@ def main():
         "pct_of_int8_mfma_peak": 100.0 * tops / INT8_MFMA_PEAK_TOPS,
         "hbm_algorithmic_gbs": alg_bytes / (dt / K) / 1e9,
         "pct_of_hbm_peak_algorithmic": 100.0 * alg_bytes / (dt / K) / 1e9 / HBM_PEAK_GBS,
+        "timed_region": ("%d replays of one HIP graph holding the step's six kernels" % K) if use_graph
+                        else ("%d eager steps" % K),
         "stage_ms": stage_ms,
         "roofline": roofline,
     }
+    if not args.no_extra and not args.sharp:
+        # The same step on the sharp-attention variant of the weights (non-degenerate softmax: a few
+        # per cent of the P levels are non-zero, activations after the projection differ per token):
+        # the figure that reflects real data; `value` stays on the weights as stated.
+        st_s = wl.block_steps(name, True, bw, ba)
+        w_s = wl.block_weights(name, sharp=True)
+        wd_s = {}
+        for nm in ("qkv", "proj", "fc1", "fc2"):
+            if "w_" + nm not in w_s:
+                continue
+            w = torch.from_numpy(w_s["w_" + nm]).cuda()
+            sw_ = vitq.vq_weight_steps(w, bw)
+            q = vitq.QMat.empty(w.shape[0], w.shape[1], bw)
+            vitq.vq_quantize(w, 0.0, sw_, q)
+            wd_s["w_" + nm], wd_s["sw_" + nm] = q, sw_
+            wd_s["b_" + nm] = torch.from_numpy(w_s["b_" + nm]).cuda()
+            if args.prepack and q.storage_bits in (2, 4) and sa == 4:
+                wd_s["wp_" + nm] = vitq.vq_prepack_weight(q)
+        desc_s = vitq.make_block_desc(dims, ba, ba, sa, wd_s, st_s)
+        sec_s = timed(make_step(desc_s, tokens, xq, y, ws, st_s["s_x"]), use_graph)
+        out.setdefault("extra", {})["sharp"] = {"ms_per_step": sec_s * 1e3, "value": B / sec_s * ops_img / 1e12, "unit": "TOPS",
+                              "images_per_s": B / sec_s,
+                              "note": "same step and timing method, sharp-attention weights (outside `value`)"}
     if not args.no_extra:
         # Outside the step (not part of `value`): the LayerNorm + comparator-quantizer glue kernel of
         # Sec. IV-C on the same token matrix, timed on its own with HIP events.
         gam = torch.ones(D, device="cuda")
         bet = torch.zeros(D, device="cuda")
         lq = vitq.QMat.empty(B * N, D, ba)
-        e0, e1 = hip.event(), hip.event()
         for i in range(4):
             if i == 1:
                 hip.record(e0, stream)
@@ -242,9 +319,9 @@ def main():
         torch.cuda.synchronize()
         ln_ms = hip.elapsed_ms(e0, e1) / 3
         ln_bytes = B * N * D * 4 + B * N * D * sa // 8
-        out["extra"] = {"vq_layernorm_quantize": {"ms": ln_ms, "rows": B * N, "cols": D,
-                                                  "algorithmic_gbs": ln_bytes / (ln_ms * 1e-3) / 1e9,
-                                                  "note": "not part of the step; fp32 in, packed levels out"}}
+        out.setdefault("extra", {})["vq_layernorm_quantize"] = {
+            "ms": ln_ms, "rows": B * N, "cols": D, "algorithmic_gbs": ln_bytes / (ln_ms * 1e-3) / 1e9,
+            "note": "not part of the step; fp32 in, packed levels out"}
         # Outside the step: the same chain with per-head LayerNorm quantizers on Q and K (the paper's
         # own attention topology, Table I); nominal steps 3 sigma / qmax for Q and K.
         qmax_a = float((1 << (ba - 1)) - 1)

@@ -360,6 +360,17 @@ vq_status vq_vit_encoder_workspace(const vq_preln_desc *layers, int32_t n_layers
 vq_status vq_vit_encoder(const vq_preln_desc *layers, int32_t n_layers, const float *x, int64_t B,
                          float *y_out, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Measurement aid (not part of the method): enqueues a register-resident loop of the int8 matrix
+ * instruction the linears run on (v_mfma_i32_32x32x32_i8, operands of the kind the kernels feed,
+ * no memory traffic) on every compute unit: `iters` x 4 instructions per wave, 4 waves per SIMD.
+ * *ops_out (host, nullable) receives the integer operations the launch performs (2 per MAC);
+ * timing it with events gives the matrix-core rate this machine sustains, which bench.py reports as
+ * roofline.peak_measured next to the published peak.  sink: device int32[1] or NULL (never
+ * written in practice).  Errors: VQ_ERR_SHAPE (iters outside 1..2^22), VQ_ERR_HIP.
+ */
+vq_status vq_probe_mfma_i8(int32_t iters, int32_t *sink, double *ops_out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libvitq.so")
-SOURCES = ["api.hip", "gemm.hip", "attention.hip", "quantize.hip", "layernorm.hip", "gemm_f6.hip"]
+SOURCES = ["api.hip", "gemm.hip", "attention.hip", "quantize.hip", "layernorm.hip", "gemm_f6.hip", "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-fno-fast-math", "-Wall", "-Wno-unused-function",
