@@ -99,6 +99,7 @@ vq_status vq_quantize(const float *x, int64_t rows, int64_t cols, int64_t ld, fl
  * y_out: device fp32 [M x Nout] or NULL.  yq_out: destination descriptor or NULL
  * (rows = M, cols = Nout); s_y is its per-tensor step (host scalar).
  * Supported (weight storage, activation storage) pairs: (4,4), (2,4), (8,8).
+ * Limits: K <= 65536; row strides of both operands below 2^24 bytes (VQ_ERR_STRIDE).
  * Errors: NULL, SHAPE (K mismatch, K > 65536, sizes overflowing int32 indexing), BITS,
  * STRIDE, STEP (s_x or s_y not positive finite), UNSUPPORTED.
  */
@@ -293,6 +294,7 @@ vq_status vq_attention_block_workspace(const vq_block_desc *desc, int64_t B, siz
 /*
  * xq: packed [B*N x D] tokens (step desc->s_x).  y_out: device fp32 [B*N x D].
  * workspace: device, 256-byte aligned, at least the size reported above.
+ * Limits: 64-channel heads, N <= 592, B*N < 2^22 token rows (VQ_ERR_SHAPE beyond).
  */
 vq_status vq_attention_block(const vq_block_desc *desc, const vq_qmat *xq, int64_t B,
                              float *y_out, void *workspace, size_t workspace_bytes,
@@ -354,7 +356,9 @@ vq_status vq_vit_block(const vq_preln_desc *desc, const float *x, int64_t B, flo
  * writes y_out, every further layer updates y_out in place.  layers: HOST array of n_layers
  * descriptors that agree in D, H, N, bit widths and storage (else VQ_ERR_SHAPE); the dump
  * pointers of the descriptors are honoured per layer.  The workspace is shared by the layers:
- * vq_vit_encoder_workspace reports the largest need.  x may be y_out (as above).
+ * vq_vit_encoder_workspace reports the largest need.  x may be y_out (as above).  The argument
+ * checks of ALL layers run before the first launch: a bad descriptor in any layer leaves y_out
+ * untouched.
  */
 vq_status vq_vit_encoder_workspace(const vq_preln_desc *layers, int32_t n_layers, int64_t B, size_t *bytes);
 vq_status vq_vit_encoder(const vq_preln_desc *layers, int32_t n_layers, const float *x, int64_t B,

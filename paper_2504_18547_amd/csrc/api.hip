@@ -102,6 +102,8 @@ vq_status check_linear_operands(const vq_qmat *xq, const vq_qmat *wq) {
     if ((st = check_qmat(wq, 0)) != VQ_OK) return st;
     if (xq->cols != wq->cols) return VQ_ERR_SHAPE;
     if (xq->cols > 65536) return VQ_ERR_SHAPE;
+    // the kernels keep a lane's operand offset inside a tile (up to 255 rows) in 32 bits
+    if (xq->row_stride >= (1 << 24) || wq->row_stride >= (1 << 24)) return VQ_ERR_STRIDE;
     if (!pair_supported(wq->storage_bits, xq->storage_bits)) return VQ_ERR_UNSUPPORTED;
     return VQ_OK;
 }
@@ -505,6 +507,9 @@ vq_status block_check(const vq_block_desc *d, int64_t B, BlockLayout *L) {
     if (d->bits_a < 2 || d->bits_a > d->storage_a) return VQ_ERR_BITS;
     if (d->bits_p < 2 || d->bits_p > d->storage_a) return VQ_ERR_BITS;
     if ((int64_t)B * d->N > INT32_MAX / 4 || (int64_t)B * d->H * d->N > INT32_MAX / 4) return VQ_ERR_SHAPE;
+    // the head-major store of the QKV linear splits a token row into (image, token) with an fp32
+    // reciprocal that is exact below 2^22 rows
+    if ((int64_t)B * d->N >= (1 << 22)) return VQ_ERR_SHAPE;
     L->M = B * d->N; L->sa = d->storage_a; L->dh = 64;
     L->act_row = (int64_t)d->D * L->sa / 8;
     L->h_row = (int64_t)d->hidden * L->sa / 8;
@@ -741,17 +746,17 @@ vq_status vq_vit_block_workspace(const vq_preln_desc *desc, int64_t B, size_t *b
     return VQ_OK;
 }
 
-vq_status vq_vit_block(const vq_preln_desc *desc, const float *x, int64_t B, float *y_out, void *workspace,
-                       size_t workspace_bytes, void *stream_) {
+namespace {
+
+// Every host-side check of vq_vit_block (nothing is launched here).
+vq_status vit_block_check(const vq_preln_desc *desc, const float *x, int64_t B, const float *y_out,
+                          const void *workspace, size_t workspace_bytes, BlockLayout *L, AttnParams *ap) {
     if (!desc) return VQ_ERR_NULL;
     const vq_block_desc *d = &desc->block;
-    BlockLayout L;
-    vq_status st = block_check(d, B, &L);
+    vq_status st = block_check(d, B, L);
     if (st != VQ_OK) return st;
     if (d->hidden <= 0) return VQ_ERR_SHAPE;
-    hipStream_t stream = (hipStream_t)stream_;
-    AttnParams ap{};
-    if ((st = block_args_check(d, L, &ap)) != VQ_OK) return st;
+    if ((st = block_args_check(d, *L, ap)) != VQ_OK) return st;
     if (!(desc->ln_eps >= 0.0f) || !isfinite(desc->ln_eps)) return VQ_ERR_STEP;
     if (!desc->ln1_gamma || !desc->ln1_beta || !desc->ln2_gamma || !desc->ln2_beta) return VQ_ERR_NULL;
     if (B == 0) return VQ_OK;
@@ -759,15 +764,22 @@ vq_status vq_vit_block(const vq_preln_desc *desc, const float *x, int64_t B, flo
     {   // in place is fine (x is last read as the residual, element by element, by the lane that then
         // writes x1 there); any other overlap is not
         const uintptr_t xa = (uintptr_t)x, ya = (uintptr_t)y_out;
-        const uintptr_t bytes = (uintptr_t)L.M * (uintptr_t)d->D * sizeof(float);
+        const uintptr_t bytes = (uintptr_t)L->M * (uintptr_t)d->D * sizeof(float);
         if (xa != ya && xa < ya + bytes && ya < xa + bytes) return VQ_ERR_STRIDE;
     }
-    const size_t xq_bytes = align256((size_t)(L.M * L.act_row));
-    if (!workspace || workspace_bytes < L.total + xq_bytes) return VQ_ERR_WORKSPACE;
+    const size_t xq_bytes = align256((size_t)(L->M * L->act_row));
+    if (!workspace || workspace_bytes < L->total + xq_bytes) return VQ_ERR_WORKSPACE;
     if (((uintptr_t)workspace) % 256 != 0) return VQ_ERR_WORKSPACE;
     if (((uintptr_t)y_out) % 16 != 0 || ((uintptr_t)x) % 16 != 0 || ((uintptr_t)desc->dump_xq) % 16 != 0)
         return VQ_ERR_STRIDE;
+    return VQ_OK;
+}
 
+// The launches of vq_vit_block, after vit_block_check has passed.
+vq_status vit_block_run(const vq_preln_desc *desc, const BlockLayout &L, const AttnParams &ap, const float *x,
+                        int64_t B, float *y_out, void *workspace, hipStream_t stream) {
+    const vq_block_desc *d = &desc->block;
+    vq_status st;
     uint8_t *ws = (uint8_t *)workspace;
     uint8_t *qkv = d->dump_qkv ? (uint8_t *)d->dump_qkv : ws + L.qkv_off;
     uint8_t *obuf = d->dump_o ? (uint8_t *)d->dump_o : ws + L.o_off;
@@ -820,6 +832,17 @@ vq_status vq_vit_block(const vq_preln_desc *desc, const float *x, int64_t B, flo
                       stream, d->wp_fc2, y_out);
 }
 
+}  // namespace
+
+vq_status vq_vit_block(const vq_preln_desc *desc, const float *x, int64_t B, float *y_out, void *workspace,
+                       size_t workspace_bytes, void *stream) {
+    BlockLayout L;
+    AttnParams ap{};
+    vq_status st = vit_block_check(desc, x, B, y_out, workspace, workspace_bytes, &L, &ap);
+    if (st != VQ_OK || B == 0) return st;
+    return vit_block_run(desc, L, ap, x, B, y_out, workspace, (hipStream_t)stream);
+}
+
 vq_status vq_vit_encoder_workspace(const vq_preln_desc *layers, int32_t n_layers, int64_t B, size_t *bytes) {
     if (!layers || !bytes) return VQ_ERR_NULL;
     if (n_layers < 1) return VQ_ERR_SHAPE;
@@ -844,8 +867,20 @@ vq_status vq_vit_encoder(const vq_preln_desc *layers, int32_t n_layers, const fl
     vq_status st = vq_vit_encoder_workspace(layers, n_layers, B, &need);
     if (st != VQ_OK) return st;
     if (workspace_bytes < need) return VQ_ERR_WORKSPACE;
+    // every layer's whole argument check first: nothing is enqueued, and y_out stays untouched,
+    // unless all of them pass
     for (int32_t i = 0; i < n_layers; ++i) {
-        st = vq_vit_block(&layers[i], i == 0 ? x : y_out, B, y_out, workspace, workspace_bytes, stream);
+        BlockLayout L;
+        AttnParams ap{};
+        st = vit_block_check(&layers[i], i == 0 ? x : y_out, B, y_out, workspace, workspace_bytes, &L, &ap);
+        if (st != VQ_OK) return st;
+    }
+    if (B == 0) return VQ_OK;
+    for (int32_t i = 0; i < n_layers; ++i) {
+        BlockLayout L;
+        AttnParams ap{};
+        (void)vit_block_check(&layers[i], i == 0 ? x : y_out, B, y_out, workspace, workspace_bytes, &L, &ap);
+        st = vit_block_run(&layers[i], L, ap, i == 0 ? x : y_out, B, y_out, workspace, (hipStream_t)stream);
         if (st != VQ_OK) return st;
     }
     return VQ_OK;

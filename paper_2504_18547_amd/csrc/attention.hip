@@ -475,7 +475,7 @@ hipError_t launch_mode(const AttnParams &p, AttnMode mode, hipStream_t stream) {
 // Every value is produced by the same arithmetic as above (integer max and sum, table / exact
 // exponential, guarded fp32 quantizer with the 64-bit fallback), so the results are identical;
 // only a handful of registers hold scores at any time, and the key count is a run-time value.
-constexpr int kStreamThreads = 1024;    // 8 waves share one head's K / V^T in LDS
+constexpr int kStreamThreads = 1024;    // 16 waves share one head's K / V^T in LDS
 
 template <int SB, bool P8, bool LUT>
 __global__ __launch_bounds__(kStreamThreads, 2) void attention_stream_kernel(AttnParams p) {

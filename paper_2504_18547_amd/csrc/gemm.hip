@@ -328,7 +328,11 @@ __device__ __forceinline__ void epilogue_quant(const GemmParams &p, const v16i &
         u32 worst = force_exact ? 0x7F800000u : 0u;
         u32 fig[8];
         u32 limit;
+#ifdef VITQ_X_FREEGELU
+        if constexpr (false) {
+#else
         if constexpr (GELU) {
+#endif
             const float gguard = p.gelu_guard * r_y;
             limit = __float_as_uint(0.5f - p.eps0);
 #pragma unroll
@@ -496,10 +500,12 @@ __device__ __forceinline__ void epilogue_headnorm(const GemmParams &p, v16i (&ac
 // most 15 per channel, else every sixteenth one (T[15], T[31], ...), which settles the first four
 // strides; the last four then probe one 16-entry stretch of the caller's table in global memory.
 constexpr int kAbsRow = 17;
-template <bool TBL_LDS>
+// WIDE: acc + b_int may leave 32 bits (see the staging of the biases): sums and comparisons in 64 bits.
+template <bool TBL_LDS, bool WIDE>
 __device__ __forceinline__ void epilogue_absorbed(const GemmParams &p, const v16i &acc, int shift, uint8_t *dst,
                                                   const int *lds_tbl, const int *glb_tbl, int64_t glb_row, const int *bint) {
     if (!dst) return;
+    using sum_t = std::conditional_t<WIDE, int64_t, int>;
     const int nthr = p.ab_nthr;
     float lv[16];
 #pragma unroll
@@ -509,23 +515,29 @@ __device__ __forceinline__ void epilogue_absorbed(const GemmParams &p, const v16
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int r = 4 * q + i;
-            const int a = (acc[r] >> shift) + bq[i];
+            const sum_t a = (sum_t)(acc[r] >> shift) + (sum_t)bq[i];
             int pos = 0;                                // references known to be exceeded
             if constexpr (TBL_LDS) {
+                // (a missing reference is INT32_MAX "never exceeded": a 64-bit sum above it can only
+                // occur with every real reference exceeded too, and pos is capped at their number)
 #pragma unroll
-                for (int step = 8; step >= 1; step >>= 1)
-                    pos += (a > lds_tbl[r * kAbsRow + pos + step - 1]) ? step : 0;
+                for (int step = 8; step >= 1; step >>= 1) {
+                    const int t = pos + step - 1;
+                    pos += ((!WIDE || t < nthr) && a > (sum_t)lds_tbl[r * kAbsRow + t]) ? step : 0;
+                }
             } else {
                 // strides 128..16 probe T[16(i+1) - 1]: entry i of the LDS row; strides 8..1 finish
                 // inside one 16-entry stretch of the caller's table
 #pragma unroll
-                for (int step = 128; step >= 16; step >>= 1)
-                    pos += (a > lds_tbl[r * kAbsRow + ((pos + step) >> 4) - 1]) ? step : 0;
+                for (int step = 128; step >= 16; step >>= 1) {
+                    const int t = pos + step - 1;
+                    pos += ((!WIDE || t < nthr) && a > (sum_t)lds_tbl[r * kAbsRow + ((pos + step) >> 4) - 1]) ? step : 0;
+                }
 #pragma unroll
                 for (int step = 8; step >= 1; step >>= 1) {
                     const int t = pos + step - 1;
                     const int v = glb_tbl[(int64_t)r * glb_row + min(t, nthr - 1)];
-                    pos += (a > (t >= nthr ? INT32_MAX : v)) ? step : 0;
+                    pos += (a > (t >= nthr ? (sum_t)INT32_MAX : (sum_t)v) && (!WIDE || t < nthr)) ? step : 0;
                 }
             }
             lv[r] = (float)pos;
@@ -727,9 +739,16 @@ void gemm_kernel(GemmParams p) {
     // folded in.  The fold is exact unless the result is subnormal; a flag then sends the whole
     // tile through the exact operation sequence.
     if constexpr (ABSORBED) {
-        // per channel: the equivalent bias
-        for (int c = tid; c < TC; c += NT)
-            reinterpret_cast<int *>(s_raw)[c] = p.ab_bint ? p.ab_bint[min(c0 + c, p.Nout - 1)] : 0;
+        // per channel: the equivalent bias.  |acc| stays below 2^23 (K <= 65536), so acc + b_int fits
+        // 32 bits unless a bias lies within 2^23 of the int32 limits (a near-dead channel): such a
+        // tile takes the 64-bit form of the comparisons.
+        if (tid == 0) s_fold_bad[0] = 0;
+        __syncthreads();
+        for (int c = tid; c < TC; c += NT) {
+            const int b = p.ab_bint ? p.ab_bint[min(c0 + c, p.Nout - 1)] : 0;
+            reinterpret_cast<int *>(s_raw)[c] = b;
+            if (b > INT32_MAX - (1 << 23) || b < INT32_MIN + (1 << 23)) s_fold_bad[0] = 1;
+        }
     } else if constexpr (EPI != kEpiGeneric) {
         if (tid == 0) s_fold_bad[0] = 0;
         __syncthreads();
@@ -1015,6 +1034,7 @@ void gemm_kernel(GemmParams p) {
             // The pipeline buffers are free now: the tile's LDS table (see epilogue_absorbed) goes there.
             const int nthr = p.ab_nthr;
             constexpr bool in_lds = (EPI == kEpiAbsorbed);
+            const bool wide = s_fold_bad[0] != 0;          // (read before the barrier below, written before the main loop)
             int *s_tbl = reinterpret_cast<int *>(smem);
             static_assert(TC * kAbsRow * 4 <= S * STAGE, "reference table exceeds the pipeline buffers");
 #pragma unroll
@@ -1040,9 +1060,12 @@ void gemm_kernel(GemmParams p) {
                     uint8_t *dst = (ch_part >= 0 && tok_part[ti] >= 0) ? p.yq + tok_part[ti] + ch_part : nullptr;
                     if (cb >= p.Nout)
                         store_zero_group(p, dst);
+                    else if (wide)
+                        epilogue_absorbed<in_lds, true>(p, acc[ci][ti], shift, dst, s_tbl + cl * kAbsRow,
+                                                        p.ab_thr + (int64_t)min(cb, p.Nout - 16) * nthr, nthr, bint);
                     else
-                        epilogue_absorbed<in_lds>(p, acc[ci][ti], shift, dst, s_tbl + cl * kAbsRow,
-                                                  p.ab_thr + (int64_t)min(cb, p.Nout - 16) * nthr, nthr, bint);
+                        epilogue_absorbed<in_lds, false>(p, acc[ci][ti], shift, dst, s_tbl + cl * kAbsRow,
+                                                         p.ab_thr + (int64_t)min(cb, p.Nout - 16) * nthr, nthr, bint);
                 });
             });
             return;

@@ -3,14 +3,14 @@
 //
 // Phase 1 -- row statistics.  They are the incremental recurrences of Eq. 5 in fp32, elements in
 // order: that order is part of the definition (fp32 addition does not associate), so one LANE
-// walks one row and the parallelism is across the 256 rows of a workgroup (4 of its 16 waves).  The lane streams
+// walks one row and the parallelism is across the 64 rows of a workgroup (one of its four waves).  The lane streams
 // its row in chunks of 16 elements, the next chunk requested before the current one is used.
 // Phase 2 -- levels.  The quantizer is the comparator of Fig. 5(b): the level is the number of
 // references (k - 1/2)*step that the normalised value exceeds, each decided as
 //     ssq((x - mu) * gamma) * n  >  ssq((k - 1/2)*step - beta) * V,      ssq(v) = v * |v|,
 // V = M_n + n*eps the (stabilised) sum of squared deviations -- sigma never appears.  Elements
 // are independent here, so the workgroup's rows are re-read wave by wave with coalesced 16-byte
-// loads by all 16 waves, four elements per lane, four rows per batch, the next batch in flight.  The comparisons are monotone in k, so
+// loads by all four waves, four elements per lane, four rows per batch, the next batch in flight.  The comparisons are monotone in k, so
 // instead of all 2^b - 1 of them the kernel makes a guess with the hardware reciprocal square
 // root and then evaluates the comparator itself only at the guessed level and the one above,
 // stepping the guess until both agree; the guess only chooses which comparisons are made, every
@@ -41,7 +41,7 @@ struct RkTable {
 __device__ const RkTable g_rk{};
 
 constexpr int kLnRows = 64;       // rows per workgroup (one lane each in phase 1)
-constexpr int kLnThreads = 256;   // threads per workgroup: all sixteen waves work in phase 2
+constexpr int kLnThreads = 256;   // threads per workgroup: all four waves work in phase 2
 constexpr int kLnWaves = kLnThreads / 64;
 
 template <bool VEC, int SB>

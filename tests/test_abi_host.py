@@ -1,10 +1,14 @@
 """The C-ABI library loads, exports what include/vitq.h declares, and rejects bad arguments on
 the host before touching the GPU (CPU only: no call here reaches a launch)."""
 import ctypes as C
+
+import numpy as np
 import os
 import re
 
 import pytest
+
+from oracle import vqo
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -197,3 +201,93 @@ def test_opcount_reproduces_table1():
     m = opcount.block_macs(384, 6, 198)
     assert m["qkv"] == 3 * 6 * c["linear_mac"] and m["qk"] == 6 * c["qk_mac"] and m["pv"] == 6 * c["pv_mac"]
     assert round(opcount.block_ops(768, 12, 197, 3072) / 1e6, 1) == 2907.9
+
+# ---- vq_absorb_thresholds: host arithmetic of the library against the oracle's (no GPU involved) ----
+def test_library_host_helper_reproduces_the_oracle_integers():
+    # vq_absorb_thresholds is host arithmetic (no GPU): written independently in the library, it
+    # must land on the same integers as the oracle for every bit width
+    from paper_2504_18547_amd import vitq
+    rng = np.random.default_rng(40)
+    for bits in (2, 3, 4, 5, 8):
+        n = 64
+        s_w = rng.uniform(1e-4, 0.05, n).astype(np.float32)
+        bias = rng.normal(0, 0.3, n).astype(np.float32)
+        s_y = rng.uniform(0.01, 0.5, n).astype(np.float32)
+        s_x = np.float32(rng.uniform(0.01, 0.2))
+        for b, sy in ((bias, s_y), (None, s_y[:1])):
+            got = vitq.vq_absorb_thresholds(s_x, s_w, b, sy, bits)
+            want = vqo.absorb(s_x, s_w, b, sy, bits, Nout=n)
+            assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1])
+
+
+def test_library_host_helper_rejects_bad_arguments():
+    from paper_2504_18547_amd import vitq
+    s_w = np.float32([0.01, 0.02])
+    code = lambda name: vitq.STATUS_NAMES.index(name)
+    for bits in (1, 9):
+        with pytest.raises(vitq.VitqError) as e:
+            vitq.vq_absorb_thresholds(0.1, s_w, None, [0.1], bits)
+        assert e.value.status == code("VQ_ERR_BITS")
+    for s_x, sw, sy in ((0.0, s_w, [0.1]), (0.1, np.float32([0.01, -1.0]), [0.1]), (0.1, s_w, [float("inf")]),
+                        (1e-30, np.float32([1e-30, 1.0]), [0.1])):          # the last: s_x*s_w underflows to zero
+        with pytest.raises(vitq.VitqError) as e:
+            vitq.vq_absorb_thresholds(s_x, sw, None, sy, 4)
+        assert e.value.status == code("VQ_ERR_STEP")
+
+
+def test_limits_are_argument_errors_not_launch_failures(lib):
+    """Sizes the kernels' 32-bit indexing cannot take are refused on the host with the codes the header lists."""
+    from paper_2504_18547_amd import vitq
+    E = {n: i for i, n in enumerate(vitq.STATUS_NAMES)}
+    fake = C.c_void_p(0x2000)
+    w = _qm(vitq, 8, 64, 4, 4)
+    x_wide = _qm(vitq, 10, 64, 4, 4, stride=1 << 24)
+    assert lib.vq_linear(C.byref(x_wide), C.c_float(1.0), C.byref(w), fake, 1, None, 0, fake, None, C.c_float(1.0),
+                         None, None) == E["VQ_ERR_STRIDE"]
+    d = vitq.vq_block_desc()
+    d.D, d.H, d.N, d.hidden, d.bits_a, d.bits_p, d.storage_a = 128, 2, 512, 256, 4, 4, 4
+    n = C.c_size_t()
+    assert lib.vq_attention_block_workspace(C.byref(d), (1 << 13) - 1, C.byref(n)) == 0
+    assert lib.vq_attention_block_workspace(C.byref(d), 1 << 13, C.byref(n)) == E["VQ_ERR_SHAPE"]      # 2^22 token rows
+    # the entry point without a workspace refuses what its static array cannot hold, before any GPU call
+    d.N = 50
+    xq = _qm(vitq, 4000 * 50, 128, 4, 4)
+    assert lib.vq_attention_block_static(C.byref(d), C.byref(xq), 4000, fake, None) == E["VQ_ERR_WORKSPACE"]
+
+
+def _fake_preln_desc(vitq, D=128, H=2, N=50, hidden=256):
+    """A descriptor whose every pointer is a (never dereferenced) fake address: passes all host checks."""
+    d = vitq.vq_preln_desc()
+    b = d.block
+    b.D, b.H, b.N, b.hidden, b.bits_a, b.bits_p, b.storage_a = D, H, N, hidden, 4, 4, 4
+    for nm, (r, c) in dict(w_qkv=(3 * D, D), w_proj=(D, D), w_fc1=(hidden, D), w_fc2=(D, hidden)).items():
+        setattr(b, nm, _qm(vitq, r, c, 4, 4))
+    for nm in ("sw_qkv", "b_qkv", "sw_proj", "b_proj", "sw_fc1", "b_fc1", "sw_fc2", "b_fc2"):
+        setattr(b, nm, 0x3000)
+    for nm in ("s_x", "s_q", "s_k", "s_v", "s_o", "s_x2", "s_h"):
+        setattr(b, nm, 0.1)
+    b.scale = 0.125
+    d.ln1_gamma = d.ln1_beta = d.ln2_gamma = d.ln2_beta = 0x3000
+    d.ln_eps = 1e-6
+    return d
+
+
+def test_encoder_checks_every_layer_before_the_first_launch(lib):
+    """A bad descriptor in a later layer is reported by its own code, and nothing has been enqueued by
+    then (there is no GPU here: an attempted launch of layer 0 would come back as VQ_ERR_HIP instead)."""
+    from paper_2504_18547_amd import vitq
+    E = {n: i for i, n in enumerate(vitq.STATUS_NAMES)}
+    good, bad = _fake_preln_desc(vitq), _fake_preln_desc(vitq)
+    bad.block.s_h = float("nan")
+    layers = (vitq.vq_preln_desc * 3)()
+    for i, dsc in enumerate((good, good, bad)):
+        C.memmove(C.byref(layers[i]), C.byref(dsc), C.sizeof(vitq.vq_preln_desc))
+    n = C.c_size_t()
+    assert lib.vq_vit_encoder_workspace(layers, 3, 2, C.byref(n)) == 0
+    x, y, ws = C.c_void_p(0x10000), C.c_void_p(0x200000), C.c_void_p(0x400000)
+    assert lib.vq_vit_encoder(layers, 3, x, 2, y, ws, n.value, None) == E["VQ_ERR_STEP"]
+    bad.block.s_h = 0.1
+    bad.ln2_beta = None
+    C.memmove(C.byref(layers[2]), C.byref(bad), C.sizeof(vitq.vq_preln_desc))
+    assert lib.vq_vit_encoder(layers, 3, x, 2, y, ws, n.value, None) == E["VQ_ERR_NULL"]
+    assert lib.vq_vit_encoder(layers, 3, x, 2, y, ws, n.value - 1, None) == E["VQ_ERR_WORKSPACE"]

@@ -22,7 +22,7 @@ def _operands(seed, M, K, Nout, bits_w, bits_a):
     return xq, wq, s_w, bias
 
 
-def _run(xq, wq, b_int, thr, bits_w, bits_a, bits_y, want_acc=True):
+def _run(xq, wq, b_int, thr, bits_w, bits_a, bits_y, want_acc=True, sum_may_leave_int32=False):
     M, Nout = xq.shape[0], wq.shape[0]
     xd, wd = to_qmat(xq, bits_a), to_qmat(wq, bits_w)
     out = vitq.QMat.empty(M, Nout, bits_y, storage_bits=4 if bits_y <= 4 else 8)   # 2-bit levels in 4-bit fields
@@ -33,7 +33,7 @@ def _run(xq, wq, b_int, thr, bits_w, bits_a, bits_y, want_acc=True):
     vitq.vq_linear_absorbed(xd, wd, bd, td, acc, out)
     torch.cuda.synchronize()
     ref = vqo.linear_absorbed(xq, wq, b_int, thr, bits_y)
-    assert ref["overflow"] == 0
+    assert sum_may_leave_int32 or ref["overflow"] == 0
     got = from_qmat(out)
     assert np.array_equal(got, ref["yq"]), "levels differ at %d of %d" % ((got != ref["yq"]).sum(), got.size)
     assert np.array_equal(out.data.cpu().numpy(), vqo.pack(ref["yq"], out.storage_bits))
@@ -92,6 +92,35 @@ def test_irregular_reference_tables():
     ref = _run(xq, wq, b_int, thr, 4, 4, 4)
     assert set(np.unique(ref["yq"][:, 0])) <= {-8, 7}
     assert np.all(ref["yq"][:, 1] == -3)
+
+
+def test_equivalent_bias_at_the_int32_limits():
+    """b_int is clamped to int32 by the preparation step, so a near-dead channel carries INT32_MAX or
+    INT32_MIN; the sum with an accumulator of the same sign then leaves 32 bits, and the oracle
+    compares it in 64 bits.  Accumulators of both signs, references at and next to the limits."""
+    xq, wq, _, _ = _operands(21, 160, 192, 48, 4, 4)
+    rng = np.random.default_rng(22)
+    thr = np.sort(rng.integers(-3000, 3000, size=(48, 15)), axis=1).astype(np.int32)
+    b_int = rng.integers(-50, 50, 48).astype(np.int32)
+    imax, imin = 2 ** 31 - 1, -2 ** 31
+    b_int[0], thr[0, :] = imax, imax                     # exceeded only by sums above INT32_MAX
+    b_int[1], thr[1, :] = imin, imin                     # exceeded unless the sum is INT32_MIN or below
+    b_int[2], thr[2, :] = imax, np.sort(np.r_[np.full(8, imax - 1), np.full(7, imax)])
+    b_int[3], thr[3, :] = imin, np.sort(np.r_[np.full(5, imin), np.full(10, imin + 40)])
+    b_int[4], thr[4, :] = imax - 1000, imax - np.arange(15)[::-1] * 150
+    b_int[5], thr[5, :] = imin + 1000, imin + np.arange(15) * 150
+    b_int[17], thr[17, :] = imax, np.sort(rng.integers(-3000, 3000, 15))   # ordinary references, huge bias
+    b_int[33], thr[33, :] = imin, np.sort(rng.integers(-3000, 3000, 15))
+    ref = _run(xq, wq, b_int, thr, 4, 4, 4, sum_may_leave_int32=True)
+    acc = ref["acc"]
+    assert (acc[:, 0] > 0).any() and (acc[:, 0] < 0).any()                 # both signs meet the limits
+    assert len(np.unique(ref["yq"][:, 0])) == 2 and len(np.unique(ref["yq"][:, 1])) == 2
+    assert np.all(ref["yq"][:, 17] == 7) and np.all(ref["yq"][:, 33] == -8)
+    # the same through the two-level table of more than fifteen references per channel
+    thr8 = np.sort(rng.integers(-3000, 3000, size=(48, 255)), axis=1).astype(np.int32)
+    thr8[0, :], thr8[1, :] = imax, imin
+    thr8[2, :128], thr8[2, 128:] = imax - 1, imax
+    _run(xq, wq, b_int, thr8, 4, 4, 8, sum_may_leave_int32=True)
 
 
 def test_argument_errors():

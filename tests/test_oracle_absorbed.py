@@ -133,36 +133,3 @@ def test_per_channel_output_steps_and_saturating_thresholds():
     wq = np.array([[7, 7]] * 3, np.int8)
     r = vqo.linear_absorbed(xq, wq, None, thr, 4)
     assert r["yq"][0, 2] == -8 + 7 + (1 if 98 > thr[2, 7] else 0)
-
-
-def test_library_host_helper_reproduces_the_oracle_integers():
-    # vq_absorb_thresholds is host arithmetic (no GPU): written independently in the library, it
-    # must land on the same integers as the oracle for every bit width
-    from paper_2504_18547_amd import vitq
-    rng = np.random.default_rng(40)
-    for bits in (2, 3, 4, 5, 8):
-        n = 64
-        s_w = rng.uniform(1e-4, 0.05, n).astype(np.float32)
-        bias = rng.normal(0, 0.3, n).astype(np.float32)
-        s_y = rng.uniform(0.01, 0.5, n).astype(np.float32)
-        s_x = np.float32(rng.uniform(0.01, 0.2))
-        for b, sy in ((bias, s_y), (None, s_y[:1])):
-            got = vitq.vq_absorb_thresholds(s_x, s_w, b, sy, bits)
-            want = vqo.absorb(s_x, s_w, b, sy, bits, Nout=n)
-            assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1])
-
-
-def test_library_host_helper_rejects_bad_arguments():
-    import pytest
-    from paper_2504_18547_amd import vitq
-    s_w = np.float32([0.01, 0.02])
-    code = lambda name: vitq.STATUS_NAMES.index(name)
-    for bits in (1, 9):
-        with pytest.raises(vitq.VitqError) as e:
-            vitq.vq_absorb_thresholds(0.1, s_w, None, [0.1], bits)
-        assert e.value.status == code("VQ_ERR_BITS")
-    for s_x, sw, sy in ((0.0, s_w, [0.1]), (0.1, np.float32([0.01, -1.0]), [0.1]), (0.1, s_w, [float("inf")]),
-                        (1e-30, np.float32([1e-30, 1.0]), [0.1])):          # the last: s_x*s_w underflows to zero
-        with pytest.raises(vitq.VitqError) as e:
-            vitq.vq_absorb_thresholds(s_x, sw, None, sy, 4)
-        assert e.value.status == code("VQ_ERR_STEP")

@@ -4,7 +4,7 @@ import numpy as np
 
 from oracle import vqo
 from paper_2504_18547_amd import workloads as wl
-from tests.gpu_util import preln_case
+from tests.oracle_cases import preln_case
 
 
 def test_chain_equals_stage_by_stage_composition():

@@ -3,7 +3,7 @@ import numpy as np
 
 from oracle import vqo
 from paper_2504_18547_amd import workloads as wl
-from tests.gpu_util import quantized_weights
+from tests.oracle_cases import quantized_weights
 
 
 def _case(name="deit_s_table1", images=(0, 1)):
