@@ -328,11 +328,7 @@ __device__ __forceinline__ void epilogue_quant(const GemmParams &p, const v16i &
         u32 worst = force_exact ? 0x7F800000u : 0u;
         u32 fig[8];
         u32 limit;
-#ifdef VITQ_X_FREEGELU
-        if constexpr (false) {
-#else
         if constexpr (GELU) {
-#endif
             const float gguard = p.gelu_guard * r_y;
             limit = __float_as_uint(0.5f - p.eps0);
 #pragma unroll
