@@ -44,6 +44,13 @@ __device__ __forceinline__ u32 nib_sub(u32 a, u32 b) {
     return ((a | 0x88888888u) - (b & 0x77777777u)) ^ ((a ^ ~b) & 0x88888888u);
 }
 
+// LDS byte address of a pointer into shared memory, and a 32-bit read at such an address
+typedef __attribute__((address_space(3))) const u32 lds_u32;
+__device__ __forceinline__ u32 lds_addr(const void *p) {
+    return (u32)(uintptr_t)(const __attribute__((address_space(3))) uint8_t *)p;
+}
+__device__ __forceinline__ u32 lds_read(u32 addr) { return *(lds_u32 *)(uintptr_t)addr; }
+
 // (1+r) << floor(alpha*d) in 12.20 fixed point for an integer score difference d <= 0 (Eq. 4)
 __device__ __forceinline__ u32 shift_exp_fixed(int d, float alpha) {
     float tt = alpha * (float)d;
@@ -81,48 +88,114 @@ __global__ __launch_bounds__(256, (NT <= 13 ? ((SB == 4 && !P8) ? VITQ_ATT_OCC :
     const int N = p.N;
     const int64_t row0 = (int64_t)bh * N;             // first row of this head in q/k/v/p
 
+    // ---- stage K (packed) and V^T (int8) ---------------------------------------------------
+    // Every global load of this thread is requested before anything waits on one (the table of
+    // exponentials is computed while they are in flight): a load -> store loop would pay the memory
+    // latency once per trip.
+    constexpr int KCH = KROW / 8;                     // 8-byte pieces per K row
+    constexpr int VCH = KROW / 16;                    // 16-byte pieces per V row
+    constexpr int K_ITEMS = NT * 16 * KCH, V_ITEMS = NKEYP * VCH;
+    constexpr bool BATCH = (NT <= 13);                // (the long-row variant keeps the loop: registers)
+    constexpr int K_IT = BATCH ? (K_ITEMS + 255) / 256 : 1, V_IT = BATCH ? (V_ITEMS + 255) / 256 : 1;
+    [[maybe_unused]] uint2 kreg[K_IT];
+    [[maybe_unused]] uint4 vreg[V_IT];
+    if constexpr (BATCH && MODE != kAttnPVOnly) {
+#pragma unroll
+        for (int it = 0; it < K_IT; ++it) {
+            const int id = it * 256 + tid;
+            const int n = id / KCH, c = id - n * KCH;
+            kreg[it] = make_uint2(0, 0);
+            if (id < K_ITEMS && n < N) kreg[it] = *reinterpret_cast<const uint2 *>(p.k + (row0 + n) * p.k_stride + c * 8);
+        }
+    }
+    if constexpr (BATCH && MODE != kAttnQKOnly) {
+#pragma unroll
+        for (int it = 0; it < V_IT; ++it) {
+            const int id = it * 256 + tid;
+            const int n = id / VCH, c = id - n * VCH;
+            vreg[it] = make_uint4(0, 0, 0, 0);
+            if (id < V_ITEMS && n < N) vreg[it] = *reinterpret_cast<const uint4 *>(p.v + (row0 + n) * p.v_stride + c * 16);
+        }
+    }
+    // this lane's packed query row of block qb (zeros beyond the last row); the first block's is
+    // requested here and each later one while the block before it is computed
+    const int nqb = (N + 15) / 16;
+    const int wslot = (wave + bh) & 3;                // rotate which wave gets the odd block
+    const int qb_first = blockIdx.y * 4 + wslot, qb_step = 4 * p.qsplit;
+    auto load_q = [&](int qb) {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        const int qrow = qb * 16 + li;
+        if (qb < nqb && qrow < N) {
+            const uint8_t *src = p.q + (row0 + qrow) * p.q_stride;
+            if constexpr (SB == 4) {
+                const uint2 t = *reinterpret_cast<const uint2 *>(src + 8 * g);
+                v.x = t.x; v.y = t.y;
+            } else {
+                v = *reinterpret_cast<const uint4 *>(src + 16 * g);
+            }
+        }
+        return v;
+    };
+    [[maybe_unused]] uint4 qnext = make_uint4(0, 0, 0, 0);
+    if constexpr (MODE != kAttnPVOnly) qnext = load_q(qb_first);
     if constexpr (LUT && MODE != kAttnPVOnly) {
         // entry d: the fixed-point exponential of score difference -d, by the exact operation
         // sequence; the last entry stands for every larger difference, where the value is 0
         for (int i = tid; i < p.lut_n; i += 256)
             sLUT[i] = (i == lut_last) ? 0u : shift_exp_fixed(-i, p.alpha);
     }
-    // ---- stage K (packed) and V^T (int8) ---------------------------------------------------
+    auto store_vt = [&](const uint4 &v, int n, int c) {
+        const u32 w[4] = {v.x, v.y, v.z, v.w};
+        const int pos = vt_pos(n);
+        if constexpr (SB == 4) {
+#pragma unroll
+            for (int j = 0; j < 32; ++j) {
+                int val = ((int)(w[j >> 3] << (28 - 4 * (j & 7)))) >> 28;   // sign-extended nibble
+                sVT[vt_row(32 * c + j) * VPITCH + pos] = (uint8_t)val;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                sVT[vt_row(16 * c + j) * VPITCH + pos] = (uint8_t)(w[j >> 2] >> (8 * (j & 3)));
+        }
+    };
     if constexpr (MODE != kAttnPVOnly) {
-        constexpr int CH = KROW / 8;                  // 8-byte pieces per row
-        for (int id = tid; id < NT * 16 * CH; id += 256) {
-            int n = id / CH, c = id - n * CH;
-            uint2 v = make_uint2(0, 0);
-            if (n < N) v = *reinterpret_cast<const uint2 *>(p.k + (row0 + n) * p.k_stride + c * 8);
-            *reinterpret_cast<uint2 *>(sK + n * KPITCH + c * 8) = v;
+        if constexpr (BATCH) {
+#pragma unroll
+            for (int it = 0; it < K_IT; ++it) {
+                const int id = it * 256 + tid;
+                const int n = id / KCH, c = id - n * KCH;
+                if (id < K_ITEMS) *reinterpret_cast<uint2 *>(sK + n * KPITCH + c * 8) = kreg[it];
+            }
+        } else {
+            for (int id = tid; id < K_ITEMS; id += 256) {
+                int n = id / KCH, c = id - n * KCH;
+                uint2 v = make_uint2(0, 0);
+                if (n < N) v = *reinterpret_cast<const uint2 *>(p.k + (row0 + n) * p.k_stride + c * 8);
+                *reinterpret_cast<uint2 *>(sK + n * KPITCH + c * 8) = v;
+            }
         }
     }
     if constexpr (MODE != kAttnQKOnly) {
-        constexpr int CH = KROW / 16;                 // 16-byte pieces per row
-        for (int id = tid; id < NKEYP * CH; id += 256) {
-            int n = id / CH, c = id - n * CH;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (n < N) v = *reinterpret_cast<const uint4 *>(p.v + (row0 + n) * p.v_stride + c * 16);
-            const u32 w[4] = {v.x, v.y, v.z, v.w};
-            const int pos = vt_pos(n);
-            if constexpr (SB == 4) {
+        if constexpr (BATCH) {
 #pragma unroll
-                for (int j = 0; j < 32; ++j) {
-                    int val = ((int)(w[j >> 3] << (28 - 4 * (j & 7)))) >> 28;   // sign-extended nibble
-                    sVT[vt_row(32 * c + j) * VPITCH + pos] = (uint8_t)val;
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < 16; ++j)
-                    sVT[vt_row(16 * c + j) * VPITCH + pos] = (uint8_t)(w[j >> 2] >> (8 * (j & 3)));
+            for (int it = 0; it < V_IT; ++it) {
+                const int id = it * 256 + tid;
+                const int n = id / VCH, c = id - n * VCH;
+                if (id < V_ITEMS) store_vt(vreg[it], n, c);
+            }
+        } else {
+            for (int id = tid; id < V_ITEMS; id += 256) {
+                int n = id / VCH, c = id - n * VCH;
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (n < N) v = *reinterpret_cast<const uint4 *>(p.v + (row0 + n) * p.v_stride + c * 16);
+                store_vt(v, n, c);
             }
         }
     }
     __syncthreads();
 
-    const int nqb = (N + 15) / 16;
-    const int wslot = (wave + bh) & 3;                // rotate which wave gets the odd block
-    for (int qb = blockIdx.y * 4 + wslot; qb < nqb; qb += 4 * p.qsplit) {
+    for (int qb = qb_first; qb < nqb; qb += qb_step) {
         const int qrow = qb * 16 + li;                // query row of this lane
         const bool qok = qrow < N;
         u32 pp[NCH * 4];                              // packed P^T: 4 levels per register
@@ -133,14 +206,11 @@ __global__ __launch_bounds__(256, (NT <= 13 ? ((SB == 4 && !P8) ? VITQ_ATT_OCC :
             // ---- S^T = K . Q^T ------------------------------------------------------------
             v4i qf;
             {
-                const uint8_t *src = p.q + (row0 + qrow) * p.q_stride;
+                const uint4 v = qnext;
+                qnext = load_q(qb + qb_step);
                 if constexpr (SB == 4) {
-                    uint2 v = make_uint2(0, 0);
-                    if (qok) v = *reinterpret_cast<const uint2 *>(src + 8 * g);
                     qf = unpack4_x16(v.x, v.y);
                 } else {
-                    uint4 v = make_uint4(0, 0, 0, 0);
-                    if (qok) v = *reinterpret_cast<const uint4 *>(src + 16 * g);
                     qf[0] = (int)v.x; qf[1] = (int)v.y; qf[2] = (int)v.z; qf[3] = (int)v.w;
                 }
             }
@@ -209,14 +279,17 @@ __global__ __launch_bounds__(256, (NT <= 13 ? ((SB == 4 && !P8) ? VITQ_ATT_OCC :
                 }
             }
             u32 sum = 0;
+            constexpr int LSH = SHIFT >= 2 ? SHIFT - 2 : 0;     // (the table exists at 4 bits only)
+            [[maybe_unused]] const u32 lut_hi = lds_addr(sLUT) + (u32)(mx >> LSH);
+            [[maybe_unused]] const u32 lut_cap = lds_addr(sLUT) + 4u * (u32)lut_last;
             auto exp_pass = [&](auto DIRECT) {
                 auto exp_of = [&](int sv) -> u32 {
                     if constexpr (LUT && !decltype(DIRECT)::value) {
                         // scores carry the operand factor 2^SHIFT, so (mx - sv) >> (SHIFT - 2) is the
                         // byte offset 4*d of entry d directly
-                        constexpr int LSH = SHIFT >= 2 ? SHIFT - 2 : 0;     // (the table exists at 4 bits only)
-                        const u32 off = min((u32)(mx - sv) >> LSH, 4u * (u32)lut_last);
-                        return *reinterpret_cast<const u32 *>(reinterpret_cast<const uint8_t *>(sLUT) + off);
+                        // (both are multiples of 2^SHIFT, so the shift distributes over the difference;
+                        // lut_hi = table address + (mx >> LSH), lut_cap = address of the last entry)
+                        return lds_read(min(lut_hi - (u32)(sv >> LSH), lut_cap));
                     } else {
                         return shift_exp_fixed(sv - mx, p.alpha_scaled);
                     }
@@ -477,8 +550,9 @@ hipError_t launch_mode(const AttnParams &p, AttnMode mode, hipStream_t stream) {
 // only a handful of registers hold scores at any time, and the key count is a run-time value.
 constexpr int kStreamThreads = 1024;    // 16 waves share one head's K / V^T in LDS
 
+// (eight waves per SIMD, i.e. at most 64 registers: two workgroups share a CU when their LDS fits)
 template <int SB, bool P8, bool LUT>
-__global__ __launch_bounds__(kStreamThreads, 2) void attention_stream_kernel(AttnParams p) {
+__global__ __launch_bounds__(kStreamThreads, 8) void attention_stream_kernel(AttnParams p) {
     constexpr int NTHR = kStreamThreads, NW = NTHR / 64;
     constexpr int KROW = 64 * SB / 8;
     constexpr int KPITCH = (SB == 4) ? 40 : 80;
@@ -504,25 +578,61 @@ __global__ __launch_bounds__(kStreamThreads, 2) void attention_stream_kernel(Att
     const int h = bh - b * p.H;
     const int64_t row0 = (int64_t)bh * N;
 
+    // Every global load of this thread (K, V and the first query row) is requested before anything
+    // waits on one; the table of exponentials is computed while they are in flight.
+    constexpr int KCH = KROW / 8, VCH = KROW / 16;    // 8-byte pieces per K row, 16-byte pieces per V row
+    constexpr int kMaxKeyp = 640;                     // N <= 592
+    constexpr int K_IT = (kMaxKeyp * KCH + NTHR - 1) / NTHR, V_IT = (kMaxKeyp * VCH + NTHR - 1) / NTHR;
+    uint2 kreg[K_IT];
+    uint4 vreg[V_IT];
+#pragma unroll
+    for (int it = 0; it < K_IT; ++it) {
+        const int id = it * NTHR + tid;
+        const int n = id / KCH, c = id - n * KCH;
+        kreg[it] = make_uint2(0, 0);
+        if (n < N) kreg[it] = *reinterpret_cast<const uint2 *>(p.k + (row0 + n) * p.k_stride + c * 8);
+    }
+#pragma unroll
+    for (int it = 0; it < V_IT; ++it) {
+        const int id = it * NTHR + tid;
+        const int n = id / VCH, c = id - n * VCH;
+        vreg[it] = make_uint4(0, 0, 0, 0);
+        if (n < N) vreg[it] = *reinterpret_cast<const uint4 *>(p.v + (row0 + n) * p.v_stride + c * 16);
+    }
+    const int nqb = (N + 15) / 16;
+    const int wslot = (wave + bh) % NW;
+    const int qb_first = blockIdx.y * NW + wslot, qb_step = NW * p.qsplit;
+    auto load_q = [&](int qb) {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        const int qrow = qb * 16 + li;
+        if (qb < nqb && qrow < N) {
+            const uint8_t *src = p.q + (row0 + qrow) * p.q_stride;
+            if constexpr (SB == 4) {
+                const uint2 t = *reinterpret_cast<const uint2 *>(src + 8 * g);
+                v.x = t.x; v.y = t.y;
+            } else {
+                v = *reinterpret_cast<const uint4 *>(src + 16 * g);
+            }
+        }
+        return v;
+    };
+    uint4 qnext = load_q(qb_first);
     if constexpr (LUT) {
         for (int i = tid; i < p.lut_n; i += NTHR)
             sLUT[i] = (i == lut_last) ? 0u : shift_exp_fixed(-i, p.alpha);
     }
-    {
-        constexpr int CH = KROW / 8;
-        for (int id = tid; id < nkeyp * CH; id += NTHR) {
-            int n = id / CH, c = id - n * CH;
-            uint2 v = make_uint2(0, 0);
-            if (n < N) v = *reinterpret_cast<const uint2 *>(p.k + (row0 + n) * p.k_stride + c * 8);
-            *reinterpret_cast<uint2 *>(sK + n * KPITCH + c * 8) = v;
-        }
+#pragma unroll
+    for (int it = 0; it < K_IT; ++it) {
+        const int id = it * NTHR + tid;
+        const int n = id / KCH, c = id - n * KCH;
+        if (id < nkeyp * KCH) *reinterpret_cast<uint2 *>(sK + n * KPITCH + c * 8) = kreg[it];
     }
-    {
-        constexpr int CH = KROW / 16;
-        for (int id = tid; id < nkeyp * CH; id += NTHR) {
-            int n = id / CH, c = id - n * CH;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (n < N) v = *reinterpret_cast<const uint4 *>(p.v + (row0 + n) * p.v_stride + c * 16);
+#pragma unroll
+    for (int it = 0; it < V_IT; ++it) {
+        const int id = it * NTHR + tid;
+        const int n = id / VCH, c = id - n * VCH;
+        if (id < nkeyp * VCH) {
+            const uint4 v = vreg[it];
             const u32 w[4] = {v.x, v.y, v.z, v.w};
             const int pos = vt_pos(n);
             if constexpr (SB == 4) {
@@ -540,23 +650,18 @@ __global__ __launch_bounds__(kStreamThreads, 2) void attention_stream_kernel(Att
     }
     __syncthreads();
 
-    const int nqb = (N + 15) / 16;
-    const int wslot = (wave + bh) % NW;
     const float thr_p = 0.5f - (P8 ? 0x1p-13f : 0x1p-17f);
     const u32 two_pmax = 2u * (u32)p.pmax;
-    for (int qb = blockIdx.y * NW + wslot; qb < nqb; qb += NW * p.qsplit) {
+    for (int qb = qb_first; qb < nqb; qb += qb_step) {
         const int qrow = qb * 16 + li;
         const bool qok = qrow < N;
         v4i qf;
         {
-            const uint8_t *src = p.q + (row0 + qrow) * p.q_stride;
+            const uint4 v = qnext;
+            qnext = load_q(qb + qb_step);
             if constexpr (SB == 4) {
-                uint2 v = make_uint2(0, 0);
-                if (qok) v = *reinterpret_cast<const uint2 *>(src + 8 * g);
                 qf = unpack4_x16(v.x, v.y);
             } else {
-                uint4 v = make_uint4(0, 0, 0, 0);
-                if (qok) v = *reinterpret_cast<const uint4 *>(src + 16 * g);
                 qf[0] = (int)v.x; qf[1] = (int)v.y; qf[2] = (int)v.z; qf[3] = (int)v.w;
             }
         }
@@ -599,12 +704,11 @@ __global__ __launch_bounds__(kStreamThreads, 2) void attention_stream_kernel(Att
                 direct = __builtin_amdgcn_ballot_w64(((mx - mn) >> SHIFT) >= lut_last) != 0;
             }
         }
+        constexpr int LSH = SHIFT >= 2 ? SHIFT - 2 : 0;
+        const u32 lut_hi = lds_addr(sLUT) + (u32)(mx >> LSH);
+        const u32 lut_cap = lds_addr(sLUT) + 4u * (u32)lut_last;
         auto exp_of = [&](int sv) -> u32 {
-            if (LUT && !direct) {
-                constexpr int LSH = SHIFT >= 2 ? SHIFT - 2 : 0;
-                const u32 off = min((u32)(mx - sv) >> LSH, 4u * (u32)lut_last);
-                return *reinterpret_cast<const u32 *>(reinterpret_cast<const uint8_t *>(sLUT) + off);
-            }
+            if (LUT && !direct) return lds_read(min(lut_hi - (u32)(sv >> LSH), lut_cap));
             return shift_exp_fixed(sv - mx, p.alpha_scaled);
         };
         // exponentials of one tile, zero for keys >= N
