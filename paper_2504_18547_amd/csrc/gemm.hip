@@ -921,8 +921,14 @@ void gemm_kernel(GemmParams p) {
             constexpr int ss = decltype(SS)::value;
             constexpr bool last_ss = (ss + 1 == NSS);
             // the rest of the stage whose first loads followed the previous synchronisation
+            // (a stage's groups must enter the load queue in order and ahead of the next stage's first
+            // group, which the synchronisation below issues: the waits count loads from the youngest.
+            // With a single sub-step per stage that leaves no later slot for the last group.)
             if constexpr (ss == 0) {
-                if (kt >= 1 && kt + S - 1 < nk) issue_part(kt + S - 1, I1{});
+                if (kt >= 1 && kt + S - 1 < nk) {
+                    issue_part(kt + S - 1, I1{});
+                    if constexpr (NSS == 1) issue_part(kt + S - 1, std::integral_constant<int, 2>{});
+                }
             }
             // step s = 0 runs; step s = 1 is unpacked; then the raw registers are free
             __builtin_amdgcn_sched_barrier(0);
@@ -943,7 +949,7 @@ void gemm_kernel(GemmParams p) {
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
-            if constexpr (ss == 0) {
+            if constexpr (ss == 0 && NSS > 1) {
                 if (kt >= 1 && kt + S - 1 < nk) issue_part(kt + S - 1, std::integral_constant<int, 2>{});
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -1184,7 +1190,15 @@ hipError_t gemm_launch(GemmParams p, int wb, int ab, hipStream_t stream) {
     }
     if (wb == 4 && ab == 4) return launch_epi<4, 4, VITQ_TC, VITQ_TT, VITQ_WC, VITQ_WT, VITQ_BK44, VITQ_S44, VITQ_OCC44>(p, epi, stream);
     if (wb == 2 && ab == 4) return launch_epi<2, 4, 128, 128, 2, 2, 128, 2, 4>(p, epi, stream);
-    if (wb == 8 && ab == 8) return launch_epi<8, 8, 128, 128, 2, 2, VITQ_BK88, VITQ_S88, VITQ_OCC88>(p, epi, stream);
+    if (wb == 8 && ab == 8) {
+        // 8-bit operands are read from LDS at twice the bytes per product and need no unpacking: a long
+        // contraction is bound by those reads and gains from 64x128 wave tiles (a quarter fewer fragment
+        // reads per product, at two waves per SIMD); a short one is dominated by its epilogue, which wants
+        // four waves per SIMD.
+        if (p.K >= 2048 && (epi == kEpiF32 || epi == kEpiQuant || epi == kEpiQuantGelu))
+            return launch_epi<8, 8, 128, 256, 2, 2, 64, 3, 2>(p, epi, stream);
+        return launch_epi<8, 8, 128, 128, 2, 2, VITQ_BK88, VITQ_S88, VITQ_OCC88>(p, epi, stream);
+    }
     if (wb == 8 && ab == 4) return launch_epi<8, 4, VITQ_TC, VITQ_TT, VITQ_WC, VITQ_WT, VITQ_BK84, VITQ_S84, VITQ_OCC84>(p, epi, stream);
     return hipErrorInvalidValue;
 }

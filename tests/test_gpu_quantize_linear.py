@@ -110,6 +110,28 @@ def test_linear_shapes_and_bit_widths(bits_x, bits_w, M, K, Nout):
                     prepack=True)
 
 
+@pytest.mark.parametrize("bits_x,bits_w", [(4, 4), (8, 8)])
+def test_long_contraction_single_output_kernels(bits_x, bits_w):
+    """K = 3072 over several token tiles with one output per call (the fp32-only and the packed-only
+    epilogues; 8-bit operands take their long-contraction tile configuration): every stage of the
+    software pipeline is refilled many times, and every element must be the oracle's."""
+    M, K, Nout = 600, 3072, 256
+    rng = np.random.default_rng(3072 + bits_w)
+    xq, wq, s_w, bias = _rand_case(rng, M, K, Nout, bits_x, bits_w)
+    s_x, s_y = np.float32(0.31), np.float32(0.4 if bits_x == 4 else 8.0)
+    ref = vqo.linear(xq, s_x, wq, s_w, bias=bias, s_y=s_y, bits_y=bits_x)
+    assert len(np.unique(ref["yq"])) >= 8
+    xd, wd = to_qmat(xq, bits_x), to_qmat(wq, bits_w)
+    for _ in range(3):
+        y = torch.full((M, Nout), -7.0, dtype=torch.float32, device="cuda")
+        vitq.vq_linear(xd, s_x, wd, dev(s_w), 1, dev(bias), 0, None, y, 0.0, None)
+        yq = vitq.QMat.empty(M, Nout, bits_x)
+        vitq.vq_linear(xd, s_x, wd, dev(s_w), 1, dev(bias), 0, None, None, s_y, yq)
+        torch.cuda.synchronize()
+        assert np.array_equal(y.cpu().numpy(), ref["y"])
+        assert np.array_equal(from_qmat(yq), ref["yq"])
+
+
 def test_prepacked_weights_are_the_levels_in_operand_order():
     rng = np.random.default_rng(91)
     perm = [0, 2, 4, 6, 1, 3, 5, 7, 8, 10, 12, 14, 9, 11, 13, 15]
