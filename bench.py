@@ -410,7 +410,7 @@ def main():
             del ws12
         # Outside the step, experimental: the fc2-shaped linear (hidden -> D, fp32 out) with both operands
         # re-coded as 6-bit E3M2 values on the scaled-MFMA instruction, against the int8 path.
-        if sa == 4 and hidden:
+        if sa == 4 and hidden and wd["w_fc2"].storage_bits == 4:     # (the re-coding takes 4-bit storage)
             hq = vitq.QMat.empty(B * N, hidden, ba)
             hq.data.copy_(torch.randint(0, 256, hq.data.shape, dtype=torch.uint8, device="cuda"))
             h6, w6 = vitq.vq_recode_e3m2(hq), vitq.vq_recode_e3m2(wd["w_fc2"])
