@@ -375,6 +375,17 @@ vq_status vq_vit_encoder(const vq_preln_desc *layers, int32_t n_layers, const fl
  */
 vq_status vq_probe_mfma_i8(int32_t iters, int32_t *sink, double *ops_out, void *stream);
 
+/*
+ * Measurement aid for the guard of fc1's GELU + requantizing epilogue (vq_linear with act = 1 and a
+ * packed output only): that epilogue first evaluates the activation with the hardware exp2 / rcp
+ * and accepts the level only when it lies further from a rounding boundary than the distance
+ * 2^-21 * |y| / s_y between that value and the definition's (Sec. IV-B quantizer after the
+ * activation; the GELU sequence itself is this build's reading).  This call runs through every
+ * finite nonzero fp32 y on the GPU and writes max |fast(y) - definition(y)| / |y| to worst_out
+ * (device, one fp32; 2^-22.40 on gfx950).  Errors: VQ_ERR_NULL, VQ_ERR_HIP.
+ */
+vq_status vq_probe_gelu_distance(float *worst_out, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

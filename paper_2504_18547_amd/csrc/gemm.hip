@@ -298,7 +298,7 @@ __device__ __forceinline__ void store_zero_group(const GemmParams &p, uint8_t *d
 // sits within the error bound of a rounding boundary and is redone with the definition's own
 // operations.  Beyond |T| = qmax + 2 both clamp to the same level; a NaN or infinity gives a NaN
 // fraction, whose bit pattern compares above every threshold, so it is redone too.
-// With GELU the cheap activation (hardware exp2 / rcp) is within 2^-18 * |y| * max(1,|y|) of the
+// With GELU the cheap activation (gelu_fast: hardware exp2 / rcp) is within kGeluFastBound * |y| of the
 // definition's, which widens the guard per element (there the test is on |t - rint(t)|).
 // The sixteen channels of a lane are done in two halves of eight (each with its own test and, if
 // need be, its own exact redo): the working set stays small enough for four waves per SIMD.
@@ -334,15 +334,10 @@ __device__ __forceinline__ void epilogue_quant(const GemmParams &p, const v16i &
 #pragma unroll
             for (int r = 0; r < 8; ++r) {
                 const float y = fmaf((float)acc[8 * h + r], scs[r], bs[r]);        // the definition's y, exactly
-                // 0.5*y*(1+tanh(u)) = y - y/(1 + 2^(2u*log2 e)),  2u*log2e = y*(k0 + k1*y^2)
-                const float y2 = y * y;
-                const float w = fmaf(y2, 0x1.a5a7d0p-4f, 0x1.26aec2p+1f);
-                const float X = __builtin_amdgcn_exp2f(w * y);
-                const float rc = __builtin_amdgcn_rcpf(1.0f + X);
-                const float g = fmaf(-y, rc, y);
+                const float g = gelu_fast(y);
                 const float t8 = fmaf(g, r_y, bias8);
                 const float q8 = rintf(t8);
-                fig[r] = __float_as_uint(fmaf(fabsf(y) + y2, gguard, fabsf(t8 - q8)));   // |y| + y^2 >= |y| * max(1, |y|)
+                fig[r] = __float_as_uint(fmaf(fabsf(y), gguard, fabsf(t8 - q8)));
                 lv[r] = __builtin_amdgcn_fmed3f(q8, 0.0f, top);
             }
         } else {
@@ -1180,7 +1175,7 @@ hipError_t gemm_launch(GemmParams p, int wb, int ab, hipStream_t stream) {
     if (p.yq && epi != kEpiAbsorbed && epi != kEpiAbsorbedBig) {
         for (int i = 0; i < 3; ++i) p.r_y[i] = 1.0f / p.s_y[i];
         p.eps0 = ldexpf(1.0f, (p.qmaxf > 7.5f ? 8 : 4) - 22);
-        p.gelu_guard = ldexpf(1.0f, -18);
+        p.gelu_guard = kGeluFastBound;
         // a step so small that 1/s overflows, or so large that it underflows, takes the exact path
         for (int i = 0; i < 3; ++i)
             if (!(p.r_y[i] > 0x1p-100f && p.r_y[i] < 0x1p100f)) {

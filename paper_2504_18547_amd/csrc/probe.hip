@@ -1,7 +1,8 @@
 // Measurement aid: what the matrix cores of this machine deliver to a register-resident loop of
 // v_mfma_i32_32x32x32_i8 (no memory, no LDS, no other arithmetic), with operands of the kind the
 // GEMM kernels feed (int8 values whose low nibble is zero).  bench.py times it and reports the
-// rate beside the published peak.
+// rate beside the published peak.  Second aid: the exhaustive distance between the fast GELU of the
+// linear's epilogue and the definition's, which is what that epilogue's guard rests on.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -35,6 +36,20 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(int iters, int32_t *sin
     if (s == 0x7fffffff && sink) sink[0] = s;        // keeps the loop alive; practically never true
 }
 
+// Largest |gelu_fast(y) - gelu_tanh(y)| / |y| over every finite nonzero fp32 y (bit patterns are strided
+// over the grid; the maximum is taken on the bit patterns, where unsigned order is float order).
+__global__ __launch_bounds__(256) void gelu_distance_kernel(u32 *worst) {
+    u32 m = 0;
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t b = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; b < (1ull << 32); b += stride) {
+        const float y = __uint_as_float((u32)b);
+        if (!(fabsf(y) < 3.0e38f) || y == 0.0f) continue;
+        const float r = fabsf(gelu_fast(y) - gelu_tanh(y)) / fabsf(y);
+        if (r == r) m = max(m, __float_as_uint(r));
+    }
+    atomicMax(worst, m);
+}
+
 }  // namespace
 }  // namespace vitq
 
@@ -48,4 +63,12 @@ extern "C" vq_status vq_probe_mfma_i8(int32_t iters, int32_t *sink, double *ops_
     if (hipGetLastError() != hipSuccess) return VQ_ERR_HIP;
     if (ops_out) *ops_out = (double)blocks * 4.0 * (double)iters * 4.0 * 65536.0;   // 2 * 32*32*32 per instruction
     return VQ_OK;
+}
+
+extern "C" vq_status vq_probe_gelu_distance(float *worst_out, void *stream) {
+    if (!worst_out) return VQ_ERR_NULL;
+    hipStream_t st = (hipStream_t)stream;
+    if (hipMemsetAsync(worst_out, 0, sizeof(float), st) != hipSuccess) return VQ_ERR_HIP;
+    hipLaunchKernelGGL(vitq::gelu_distance_kernel, dim3(4096), dim3(256), 0, st, reinterpret_cast<vitq::u32 *>(worst_out));
+    return hipGetLastError() == hipSuccess ? VQ_OK : VQ_ERR_HIP;
 }

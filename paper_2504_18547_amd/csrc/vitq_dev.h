@@ -71,6 +71,19 @@ __device__ __forceinline__ float gelu_tanh(float y) {
     return (0.5f * y) * (1.0f + th);
 }
 
+// The same activation from the hardware transcendentals, for a first guess that a guard then accepts or
+// sends to gelu_tanh: 0.5*y*(1+tanh(u)) = y - y/(1 + 2^(2u*log2 e)) with 2u*log2e = y*(k0 + k1*y^2).
+// Over every finite fp32 y its distance from gelu_tanh(y) is at most 2^-22.40 * |y| (exhaustive run on
+// the GPU; vq_probe_gelu_distance repeats it), so kGeluFastBound = 2^-21 * |y| bounds it with room.
+__device__ __forceinline__ float gelu_fast(float y) {
+    const float y2 = y * y;
+    const float w = fmaf(y2, 0x1.a5a7d0p-4f, 0x1.26aec2p+1f);
+    const float X = __builtin_amdgcn_exp2f(w * y);
+    const float rc = __builtin_amdgcn_rcpf(1.0f + X);
+    return fmaf(-y, rc, y);
+}
+constexpr float kGeluFastBound = 0x1p-21f;
+
 // ---------------------------------------------------------------------------------------
 // Unpacking packed low-bit fields into int8 MFMA operands WITHOUT sign extension: a signed
 // b-bit field moved to the top b bits of a byte is the int8 value 2^(8-b) * q.  The products

@@ -19,7 +19,8 @@ EXPORTS = ["vq_status_string", "vq_weight_steps", "vq_quantize", "vq_linear", "v
            "vq_matmul_pv", "vq_attention_block_workspace", "vq_attention_block",
            "vq_prepack_weight_bytes", "vq_prepack_weight", "vq_linear_prepacked", "vq_layernorm_quantize",
            "vq_vit_block_workspace", "vq_vit_block", "vq_qkv_headnorm", "vq_absorb_thresholds",
-           "vq_linear_absorbed", "vq_recode_e3m2_bytes", "vq_recode_e3m2", "vq_linear_e3m2", "vq_vit_encoder_workspace", "vq_vit_encoder", "vq_attention_block_static", "vq_probe_mfma_i8"]
+           "vq_linear_absorbed", "vq_recode_e3m2_bytes", "vq_recode_e3m2", "vq_linear_e3m2", "vq_vit_encoder_workspace", "vq_vit_encoder", "vq_attention_block_static", "vq_probe_mfma_i8",
+           "vq_probe_gelu_distance"]
 
 
 class VitqError(RuntimeError):
@@ -86,6 +87,7 @@ def lib():
         _lib.vq_attention_block.argtypes = [C.POINTER(vq_block_desc), qp, C.c_int64, vp, vp, C.c_size_t, vp]
         _lib.vq_attention_block_static.argtypes = [C.POINTER(vq_block_desc), qp, C.c_int64, vp, vp]
         _lib.vq_probe_mfma_i8.argtypes = [C.c_int32, vp, C.POINTER(C.c_double), vp]
+        _lib.vq_probe_gelu_distance.argtypes = [vp, vp]
         _lib.vq_prepack_weight_bytes.argtypes = [qp, C.POINTER(C.c_size_t)]
         _lib.vq_prepack_weight.argtypes = [qp, vp, C.c_size_t, vp]
         _lib.vq_linear_prepacked.argtypes = [qp, C.c_float, qp, vp, vp, C.c_int32, vp, C.c_int32, vp, vp,
@@ -311,6 +313,14 @@ def vq_attention_block(desc, xq, B, y_out, workspace):
 def vq_attention_block_static(desc, xq, B, y_out):
     _check(lib().vq_attention_block_static(C.byref(desc), _q(xq), int(B), _ptr(y_out), _stream()),
            "vq_attention_block_static")
+
+
+def vq_probe_gelu_distance():
+    """max over every finite nonzero fp32 y of |fast GELU - definition| / |y| (a device tensor of one float)."""
+    import torch
+    out = torch.empty(1, dtype=torch.float32, device="cuda")
+    _check(lib().vq_probe_gelu_distance(_ptr(out), _stream()), "vq_probe_gelu_distance")
+    return out
 
 
 def vq_probe_mfma_i8(iters, sink=None):

@@ -132,6 +132,62 @@ def test_long_contraction_single_output_kernels(bits_x, bits_w):
         assert np.array_equal(from_qmat(yq), ref["yq"])
 
 
+def test_fast_gelu_stays_within_the_bound_its_guard_assumes():
+    """The GELU + requantizing epilogue accepts a level from the hardware exp2 / rcp form of the activation
+    only when it is further than 2^-21 * |y| / s_y from a rounding boundary.  That is sound as long as the
+    fast form is within 2^-21 * |y| of the definition's for EVERY fp32 y: run through all of them."""
+    worst = vitq.vq_probe_gelu_distance()
+    torch.cuda.synchronize()
+    assert 0.0 < float(worst.item()) <= 2.0 ** -22, "fast GELU drifts %g * |y| from the definition" % worst.item()
+
+
+@pytest.mark.parametrize("s_y", [0.0028, 0.047, 0.35])
+def test_gelu_requant_only_output_matches_the_definition_on_dense_inputs(s_y):
+    """Packed-only output with GELU (the guarded epilogue), on y values swept densely through the range in
+    which the sixteen levels change: with zero weights y is the bias, one value per channel."""
+    M, K, Nout = 64, 64, 4096
+    lo, hi = vqo.qrange(4)
+    y_span = (hi + 1.5) * s_y + 0.2
+    bias = np.linspace(-min(4.0, 12 * y_span), y_span, Nout).astype(np.float32)
+    rng = np.random.default_rng(5)
+    bias += (rng.standard_normal(Nout) * 1e-4).astype(np.float32)
+    # ... and the fp32 neighbourhoods (+-32 ulps) of the points where the definition's level changes on the
+    # rising branch: both sides of every guard band
+    near = []
+    for k in range(lo + 1, hi + 1):
+        target = (k - 0.5) * float(s_y)
+        a_, b_ = -0.75, 20.0
+        if not (float(vqo.gelu(np.float32(a_))[0]) < target < float(vqo.gelu(np.float32(b_))[0])):
+            continue
+        for _ in range(60):
+            m_ = 0.5 * (a_ + b_)
+            if float(vqo.gelu(np.float32(m_))[0]) < target:
+                a_ = m_
+            else:
+                b_ = m_
+        y0 = np.float32(b_)
+        up, dn = y0, y0
+        near.append(y0)
+        for _ in range(32):
+            up = np.nextafter(up, np.float32(np.inf), dtype=np.float32)
+            dn = np.nextafter(dn, np.float32(-np.inf), dtype=np.float32)
+            near += [up, dn]
+    near = np.array(near, np.float32)
+    assert near.size >= 65 * 7
+    bias[:near.size] = near
+    xq = rng.integers(lo, hi + 1, (M, K)).astype(np.int8)
+    wq = np.zeros((Nout, K), np.int8)
+    s_w = np.ones(Nout, np.float32)
+    ref = vqo.linear(xq, np.float32(0.5), wq, s_w, bias=bias, act=1, s_y=np.float32(s_y), bits_y=4)
+    assert len(np.unique(ref["yq"])) >= 8
+    yq = vitq.QMat.empty(M, Nout, 4)
+    vitq.vq_linear(to_qmat(xq, 4), np.float32(0.5), to_qmat(wq, 4), dev(s_w), 1, dev(bias), 1, None, None,
+                   np.float32(s_y), yq)
+    torch.cuda.synchronize()
+    got = from_qmat(yq)
+    assert np.array_equal(got, ref["yq"]), "levels differ at y = %r" % bias[np.flatnonzero((got != ref["yq"]).any(0))[:8]]
+
+
 def test_prepacked_weights_are_the_levels_in_operand_order():
     rng = np.random.default_rng(91)
     perm = [0, 2, 4, 6, 1, 3, 5, 7, 8, 10, 12, 14, 9, 11, 13, 15]
