@@ -2,7 +2,7 @@
 // softmax division absorbed into the P quantizer's thresholds (Sec. IV-B), and O = P.V with
 // the operand scales applied next to the output quantizer (Sec. IV-B).
 //
-// One workgroup (4 waves) serves one (image, head): K (packed) and V^T (int8) are staged in
+// One workgroup (4 waves) serves one (image, head): K and V^T are staged as int8 in
 // LDS once, then each wave takes blocks of 16 query rows.  Everything between the two
 // matmuls stays in registers:
 //
@@ -51,6 +51,29 @@ __device__ __forceinline__ u32 lds_addr(const void *p) {
 }
 __device__ __forceinline__ u32 lds_read(u32 addr) { return *(lds_u32 *)(uintptr_t)addr; }
 
+// K rows in LDS.  EXPAND (the register-resident kernel): int8 MFMA operands whatever the storage, a
+// 4-bit row being expanded once per workgroup when it is staged (16 * level per byte, in the value order
+// of unpack4_x16, which the query fragments share) instead of once per 16-query block that reads it.
+// Otherwise (the streaming kernel, which reads every row three times per query block and is bound by
+// those LDS reads) 4-bit rows stay packed and a lane unpacks its fragment.  Piece c is 8 bytes of the
+// packed row; the pitches are bank-conflict-free for the fragment reads.
+template <int SB, bool EXPAND>
+struct KRows {
+    static constexpr int pitch = (SB == 4 && !EXPAND) ? 40 : 80;
+    static __device__ __forceinline__ void store_piece(uint8_t *row, int c, const uint2 &v) {
+        if constexpr (SB == 4 && EXPAND) *reinterpret_cast<v4i *>(row + 16 * c) = unpack4_x16(v.x, v.y);
+        else *reinterpret_cast<uint2 *>(row + 8 * c) = v;
+    }
+    static __device__ __forceinline__ v4i fragment(const uint8_t *row, int g) {
+        if constexpr (SB == 4 && !EXPAND) {
+            const uint2 v = *reinterpret_cast<const uint2 *>(row + 8 * g);
+            return unpack4_x16(v.x, v.y);
+        } else {
+            return *reinterpret_cast<const v4i *>(row + 16 * g);
+        }
+    }
+};
+
 // (1+r) << floor(alpha*d) in 12.20 fixed point for an integer score difference d <= 0 (Eq. 4)
 __device__ __forceinline__ u32 shift_exp_fixed(int d, float alpha) {
     float tt = alpha * (float)d;
@@ -68,7 +91,8 @@ __global__ __launch_bounds__(256, (NT <= 13 ? ((SB == 4 && !P8) ? VITQ_ATT_OCC :
     constexpr int NCH = (NT + 3) / 4;                 // 64-key chunks of the P.V contraction
     constexpr int NKEYP = NCH * 64;                   // padded key count of V^T rows
     constexpr int KROW = 64 * SB / 8;                 // bytes of one packed K row
-    constexpr int KPITCH = (SB == 4) ? 40 : 80;       // bank-conflict-free pitch for the fragment reads
+    using KR = KRows<SB, true>;
+    constexpr int KPITCH = KR::pitch;
     constexpr int VPITCH = NKEYP + 16;
     constexpr int SHIFT = (SB == 4) ? 8 : 0;          // both operands of S carry a factor 16 at 4 bits
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -88,7 +112,7 @@ __global__ __launch_bounds__(256, (NT <= 13 ? ((SB == 4 && !P8) ? VITQ_ATT_OCC :
     const int N = p.N;
     const int64_t row0 = (int64_t)bh * N;             // first row of this head in q/k/v/p
 
-    // ---- stage K (packed) and V^T (int8) ---------------------------------------------------
+    // ---- stage K and V^T (both int8) ---------------------------------------------------
     // Every global load of this thread is requested before anything waits on one (the table of
     // exponentials is computed while they are in flight): a load -> store loop would pay the memory
     // latency once per trip.
@@ -165,14 +189,14 @@ __global__ __launch_bounds__(256, (NT <= 13 ? ((SB == 4 && !P8) ? VITQ_ATT_OCC :
             for (int it = 0; it < K_IT; ++it) {
                 const int id = it * 256 + tid;
                 const int n = id / KCH, c = id - n * KCH;
-                if (id < K_ITEMS) *reinterpret_cast<uint2 *>(sK + n * KPITCH + c * 8) = kreg[it];
+                if (id < K_ITEMS) KR::store_piece(sK + n * KPITCH, c, kreg[it]);
             }
         } else {
             for (int id = tid; id < K_ITEMS; id += 256) {
                 int n = id / KCH, c = id - n * KCH;
                 uint2 v = make_uint2(0, 0);
                 if (n < N) v = *reinterpret_cast<const uint2 *>(p.k + (row0 + n) * p.k_stride + c * 8);
-                *reinterpret_cast<uint2 *>(sK + n * KPITCH + c * 8) = v;
+                KR::store_piece(sK + n * KPITCH, c, v);
             }
         }
     }
@@ -218,13 +242,7 @@ __global__ __launch_bounds__(256, (NT <= 13 ? ((SB == 4 && !P8) ? VITQ_ATT_OCC :
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
                 v4i kf;
-                const uint8_t *src = sK + (16 * t + li) * KPITCH;
-                if constexpr (SB == 4) {
-                    uint2 v = *reinterpret_cast<const uint2 *>(src + 8 * g);
-                    kf = unpack4_x16(v.x, v.y);
-                } else {
-                    kf = *reinterpret_cast<const v4i *>(src + 16 * g);
-                }
+                kf = KR::fragment(sK + (16 * t + li) * KPITCH, g);
                 v4i z = {0, 0, 0, 0};
                 s[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(kf, qf, z, 0, 0, 0);
             }
@@ -501,7 +519,7 @@ __global__ __launch_bounds__(256, (NT <= 13 ? ((SB == 4 && !P8) ? VITQ_ATT_OCC :
 template <int NT, int SB, int MODE, bool P8, bool LUT, bool TAIL>
 hipError_t launch_tail(const AttnParams &p, hipStream_t stream) {
     constexpr int NCH = (NT + 3) / 4;
-    constexpr int KPITCH = (SB == 4) ? 40 : 80;
+    constexpr int KPITCH = KRows<SB, true>::pitch;
     const size_t lds = ((NT * 16 * KPITCH + 15) & ~15) + (size_t)64 * (NCH * 64 + 16) +
                        (LUT ? (size_t)p.lut_n * 4 : 0);
     auto kern = attention_kernel<NT, SB, MODE, P8, LUT, TAIL>;
@@ -555,7 +573,8 @@ template <int SB, bool P8, bool LUT>
 __global__ __launch_bounds__(kStreamThreads, 8) void attention_stream_kernel(AttnParams p) {
     constexpr int NTHR = kStreamThreads, NW = NTHR / 64;
     constexpr int KROW = 64 * SB / 8;
-    constexpr int KPITCH = (SB == 4) ? 40 : 80;
+    using KR = KRows<SB, false>;
+    constexpr int KPITCH = KR::pitch;
     constexpr int SHIFT = (SB == 4) ? 8 : 0;
     const int N = p.N;
     const int nt = (N + 15) / 16;                     // key tiles
@@ -625,7 +644,7 @@ __global__ __launch_bounds__(kStreamThreads, 8) void attention_stream_kernel(Att
     for (int it = 0; it < K_IT; ++it) {
         const int id = it * NTHR + tid;
         const int n = id / KCH, c = id - n * KCH;
-        if (id < nkeyp * KCH) *reinterpret_cast<uint2 *>(sK + n * KPITCH + c * 8) = kreg[it];
+        if (id < nkeyp * KCH) KR::store_piece(sK + n * KPITCH, c, kreg[it]);
     }
 #pragma unroll
     for (int it = 0; it < V_IT; ++it) {
@@ -668,13 +687,7 @@ __global__ __launch_bounds__(kStreamThreads, 8) void attention_stream_kernel(Att
         // one 16-key tile of S^T: lane (query li, group g) gets keys 16t + 4g + r
         auto score_tile = [&](int t) -> v4i {
             v4i kf;
-            const uint8_t *src = sK + (16 * t + li) * KPITCH;
-            if constexpr (SB == 4) {
-                uint2 v = *reinterpret_cast<const uint2 *>(src + 8 * g);
-                kf = unpack4_x16(v.x, v.y);
-            } else {
-                kf = *reinterpret_cast<const v4i *>(src + 16 * g);
-            }
+            kf = KR::fragment(sK + (16 * t + li) * KPITCH, g);
             v4i z = {0, 0, 0, 0};
             return __builtin_amdgcn_mfma_i32_16x16x64_i8(kf, qf, z, 0, 0, 0);
         };
@@ -854,7 +867,7 @@ __global__ __launch_bounds__(kStreamThreads, 8) void attention_stream_kernel(Att
 
 template <int SB, bool P8, bool LUT>
 hipError_t launch_stream(const AttnParams &p, hipStream_t stream) {
-    constexpr int KPITCH = (SB == 4) ? 40 : 80;
+    constexpr int KPITCH = KRows<SB, false>::pitch;
     const int nch = ((p.N + 15) / 16 + 3) / 4;
     const size_t lds = (((size_t)nch * 64 * KPITCH + 15) & ~(size_t)15) + (size_t)64 * (nch * 64 + 16) +
                        (LUT ? (size_t)p.lut_n * 4 : 0);
