@@ -51,6 +51,55 @@ __device__ __forceinline__ u32 lds_addr(const void *p) {
 }
 __device__ __forceinline__ u32 lds_read(u32 addr) { return *(lds_u32 *)(uintptr_t)addr; }
 
+// V^T in LDS (int8, one row per d; a dword of a row is four consecutive keys).  An item is four keys x one
+// 4-byte piece of their V rows (eight 4-bit or four 8-bit values): the four words are transposed in
+// registers (byte permutes) and written as whole dwords, one per value -- byte-wise writes from lanes
+// holding one key each serialise four to a dword.  4-bit values are kept as 16 * q (moved to the top of
+// their byte without sign extension, like the other operands), so the P.V accumulators carry a factor
+// 2^kShift that the epilogue removes with an exact shift.
+template <int SB>
+struct VRows {
+    static constexpr int kPieces = (SB == 4) ? 8 : 16;     // 4-byte pieces per V row
+    static constexpr int kShift = (SB == 4) ? 4 : 0;
+    static __device__ __forceinline__ void load(const uint8_t *v, int64_t row0, int64_t stride, int N, int item, u32 (&w)[4]) {
+        const int kg = item / kPieces, dp = item - kg * kPieces;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int n = 4 * kg + i;
+            w[i] = 0u;
+            if (n < N) w[i] = *reinterpret_cast<const u32 *>(v + (row0 + n) * stride + 4 * dp);
+        }
+    }
+    // rows a0..a3 (one word per key) -> o[j] = byte j of each, key 0 in the low byte
+    static __device__ __forceinline__ void transpose(u32 a0, u32 a1, u32 a2, u32 a3, u32 (&o)[4]) {
+        const u32 t0 = __builtin_amdgcn_perm(a1, a0, 0x05010400u), t1 = __builtin_amdgcn_perm(a1, a0, 0x07030602u);
+        const u32 t2 = __builtin_amdgcn_perm(a3, a2, 0x05010400u), t3 = __builtin_amdgcn_perm(a3, a2, 0x07030602u);
+        o[0] = __builtin_amdgcn_perm(t2, t0, 0x05040100u);
+        o[1] = __builtin_amdgcn_perm(t2, t0, 0x07060302u);
+        o[2] = __builtin_amdgcn_perm(t3, t1, 0x05040100u);
+        o[3] = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
+    }
+    static __device__ __forceinline__ void store(uint8_t *sVT, int vpitch, int item, const u32 (&w)[4]) {
+        const int kg = item / kPieces, dp = item - kg * kPieces;
+        uint8_t *col = sVT + vt_pos(4 * kg);
+        u32 o[4];
+        if constexpr (SB == 4) {
+            // even values (low nibbles) and odd values (high nibbles) of the piece: d = 8*dp + 2*j (+1)
+            transpose((w[0] << 4) & 0xF0F0F0F0u, (w[1] << 4) & 0xF0F0F0F0u, (w[2] << 4) & 0xF0F0F0F0u,
+                      (w[3] << 4) & 0xF0F0F0F0u, o);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) *reinterpret_cast<u32 *>(col + vt_row(8 * dp + 2 * j) * vpitch) = o[j];
+            transpose(w[0] & 0xF0F0F0F0u, w[1] & 0xF0F0F0F0u, w[2] & 0xF0F0F0F0u, w[3] & 0xF0F0F0F0u, o);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) *reinterpret_cast<u32 *>(col + vt_row(8 * dp + 2 * j + 1) * vpitch) = o[j];
+        } else {
+            transpose(w[0], w[1], w[2], w[3], o);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) *reinterpret_cast<u32 *>(col + vt_row(4 * dp + j) * vpitch) = o[j];
+        }
+    }
+};
+
 // K rows in LDS.  EXPAND (the register-resident kernel): int8 MFMA operands whatever the storage, a
 // 4-bit row being expanded once per workgroup when it is staged (16 * level per byte, in the value order
 // of unpack4_x16, which the query fragments share) instead of once per 16-query block that reads it.
@@ -117,12 +166,12 @@ __global__ __launch_bounds__(256, (NT <= 13 ? ((SB == 4 && !P8) ? VITQ_ATT_OCC :
     // exponentials is computed while they are in flight): a load -> store loop would pay the memory
     // latency once per trip.
     constexpr int KCH = KROW / 8;                     // 8-byte pieces per K row
-    constexpr int VCH = KROW / 16;                    // 16-byte pieces per V row
-    constexpr int K_ITEMS = NT * 16 * KCH, V_ITEMS = NKEYP * VCH;
+    using VR = VRows<SB>;
+    constexpr int K_ITEMS = NT * 16 * KCH, V_ITEMS = (NKEYP / 4) * VR::kPieces;   // (V: four keys x one 4-byte piece)
     constexpr bool BATCH = (NT <= 13);                // (the long-row variant keeps the loop: registers)
     constexpr int K_IT = BATCH ? (K_ITEMS + 255) / 256 : 1, V_IT = BATCH ? (V_ITEMS + 255) / 256 : 1;
     [[maybe_unused]] uint2 kreg[K_IT];
-    [[maybe_unused]] uint4 vreg[V_IT];
+    [[maybe_unused]] u32 vreg[V_IT][4];
     if constexpr (BATCH && MODE != kAttnPVOnly) {
 #pragma unroll
         for (int it = 0; it < K_IT; ++it) {
@@ -136,9 +185,7 @@ __global__ __launch_bounds__(256, (NT <= 13 ? ((SB == 4 && !P8) ? VITQ_ATT_OCC :
 #pragma unroll
         for (int it = 0; it < V_IT; ++it) {
             const int id = it * 256 + tid;
-            const int n = id / VCH, c = id - n * VCH;
-            vreg[it] = make_uint4(0, 0, 0, 0);
-            if (id < V_ITEMS && n < N) vreg[it] = *reinterpret_cast<const uint4 *>(p.v + (row0 + n) * p.v_stride + c * 16);
+            VR::load(p.v, row0, p.v_stride, id < V_ITEMS ? N : 0, id, vreg[it]);
         }
     }
     // this lane's packed query row of block qb (zeros beyond the last row); the first block's is
@@ -168,21 +215,6 @@ __global__ __launch_bounds__(256, (NT <= 13 ? ((SB == 4 && !P8) ? VITQ_ATT_OCC :
         for (int i = tid; i < p.lut_n; i += 256)
             sLUT[i] = (i == lut_last) ? 0u : shift_exp_fixed(-i, p.alpha);
     }
-    auto store_vt = [&](const uint4 &v, int n, int c) {
-        const u32 w[4] = {v.x, v.y, v.z, v.w};
-        const int pos = vt_pos(n);
-        if constexpr (SB == 4) {
-#pragma unroll
-            for (int j = 0; j < 32; ++j) {
-                int val = ((int)(w[j >> 3] << (28 - 4 * (j & 7)))) >> 28;   // sign-extended nibble
-                sVT[vt_row(32 * c + j) * VPITCH + pos] = (uint8_t)val;
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < 16; ++j)
-                sVT[vt_row(16 * c + j) * VPITCH + pos] = (uint8_t)(w[j >> 2] >> (8 * (j & 3)));
-        }
-    };
     if constexpr (MODE != kAttnPVOnly) {
         if constexpr (BATCH) {
 #pragma unroll
@@ -205,15 +237,13 @@ __global__ __launch_bounds__(256, (NT <= 13 ? ((SB == 4 && !P8) ? VITQ_ATT_OCC :
 #pragma unroll
             for (int it = 0; it < V_IT; ++it) {
                 const int id = it * 256 + tid;
-                const int n = id / VCH, c = id - n * VCH;
-                if (id < V_ITEMS) store_vt(vreg[it], n, c);
+                if (id < V_ITEMS) VR::store(sVT, VPITCH, id, vreg[it]);
             }
         } else {
             for (int id = tid; id < V_ITEMS; id += 256) {
-                int n = id / VCH, c = id - n * VCH;
-                uint4 v = make_uint4(0, 0, 0, 0);
-                if (n < N) v = *reinterpret_cast<const uint4 *>(p.v + (row0 + n) * p.v_stride + c * 16);
-                store_vt(v, n, c);
+                u32 w[4];
+                VR::load(p.v, row0, p.v_stride, N, id, w);
+                VR::store(sVT, VPITCH, id, w);
             }
         }
     }
@@ -453,6 +483,7 @@ __global__ __launch_bounds__(256, (NT <= 13 ? ((SB == 4 && !P8) ? VITQ_ATT_OCC :
                     for (int r = 0; r < 4; ++r) {
                         int a = o[T][r];
                         if constexpr (P8) a += 128 * cs[T][r];
+                        a >>= VRows<SB>::kShift;         // (V^T holds 16 * q at 4 bits: exact)
                         oa[4 * T + r] = a;
                         const float ov = (float)a * p.spv;
                         of[4 * T + r] = ov;
@@ -599,11 +630,12 @@ __global__ __launch_bounds__(kStreamThreads, 8) void attention_stream_kernel(Att
 
     // Every global load of this thread (K, V and the first query row) is requested before anything
     // waits on one; the table of exponentials is computed while they are in flight.
-    constexpr int KCH = KROW / 8, VCH = KROW / 16;    // 8-byte pieces per K row, 16-byte pieces per V row
+    constexpr int KCH = KROW / 8;                     // 8-byte pieces per K row
+    using VR = VRows<SB>;                             // V items: four keys x one 4-byte piece
     constexpr int kMaxKeyp = 640;                     // N <= 592
-    constexpr int K_IT = (kMaxKeyp * KCH + NTHR - 1) / NTHR, V_IT = (kMaxKeyp * VCH + NTHR - 1) / NTHR;
+    constexpr int K_IT = (kMaxKeyp * KCH + NTHR - 1) / NTHR, V_IT = ((kMaxKeyp / 4) * VR::kPieces + NTHR - 1) / NTHR;
     uint2 kreg[K_IT];
-    uint4 vreg[V_IT];
+    u32 vreg[V_IT][4];
 #pragma unroll
     for (int it = 0; it < K_IT; ++it) {
         const int id = it * NTHR + tid;
@@ -614,9 +646,7 @@ __global__ __launch_bounds__(kStreamThreads, 8) void attention_stream_kernel(Att
 #pragma unroll
     for (int it = 0; it < V_IT; ++it) {
         const int id = it * NTHR + tid;
-        const int n = id / VCH, c = id - n * VCH;
-        vreg[it] = make_uint4(0, 0, 0, 0);
-        if (n < N) vreg[it] = *reinterpret_cast<const uint4 *>(p.v + (row0 + n) * p.v_stride + c * 16);
+        VR::load(p.v, row0, p.v_stride, id < (nkeyp / 4) * VR::kPieces ? N : 0, id, vreg[it]);
     }
     const int nqb = (N + 15) / 16;
     const int wslot = (wave + bh) % NW;
@@ -649,23 +679,7 @@ __global__ __launch_bounds__(kStreamThreads, 8) void attention_stream_kernel(Att
 #pragma unroll
     for (int it = 0; it < V_IT; ++it) {
         const int id = it * NTHR + tid;
-        const int n = id / VCH, c = id - n * VCH;
-        if (id < nkeyp * VCH) {
-            const uint4 v = vreg[it];
-            const u32 w[4] = {v.x, v.y, v.z, v.w};
-            const int pos = vt_pos(n);
-            if constexpr (SB == 4) {
-#pragma unroll
-                for (int j = 0; j < 32; ++j) {
-                    int val = ((int)(w[j >> 3] << (28 - 4 * (j & 7)))) >> 28;
-                    sVT[vt_row(32 * c + j) * vpitch + pos] = (uint8_t)val;
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < 16; ++j)
-                    sVT[vt_row(16 * c + j) * vpitch + pos] = (uint8_t)(w[j >> 2] >> (8 * (j & 3)));
-            }
-        }
+        if (id < (nkeyp / 4) * VR::kPieces) VR::store(sVT, vpitch, id, vreg[it]);
     }
     __syncthreads();
 
@@ -823,6 +837,7 @@ __global__ __launch_bounds__(kStreamThreads, 8) void attention_stream_kernel(Att
                 for (int r = 0; r < 4; ++r) {
                     int a = o[T][r];
                     if constexpr (P8) a += 128 * cs[T][r];
+                    a >>= VRows<SB>::kShift;             // (V^T holds 16 * q at 4 bits: exact)
                     const float ov = (float)a * p.spv;
                     of[4 * T + r] = ov;
                     const float t8 = fmaf(ov, p.r_o, bias8);
