@@ -24,16 +24,37 @@ __global__ __launch_bounds__(256) void quantize_kernel(QuantParams p) {
         const int64_t c0 = (int64_t)wi * PER;
         u32 word = 0;
         if (c0 + PER <= p.cols && (((uintptr_t)(src + c0)) & 15) == 0) {
+            float f[PER];
 #pragma unroll
             for (int j = 0; j < PER / 4; ++j) {
                 float4 v = reinterpret_cast<const float4 *>(src + c0)[j];
-                const float f[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    int q = quantize_level(f[i], s, p.qminf, p.qmaxf);
-                    word |= ((u32)q & ((1u << SB) - 1u)) << (SB * (4 * j + i));
-                }
+                f[4 * j] = v.x; f[4 * j + 1] = v.y; f[4 * j + 2] = v.z; f[4 * j + 3] = v.w;
             }
+            // Guarded fast path (the same scheme as the linear's requantizing epilogue): with r = RN(1/s),
+            // g = 2^(bits-22) and C = -qmin + 1/2 - g, u = fma(x, r, C) is within g of x/s - qmin + 1/2 - g
+            // for |x/s| <= qmax + 2; unless fract(u) >= 1 - 2g the level is floor(u), clamped.  A thread with
+            // an element inside the guard (or a NaN, whose fraction compares above everything as a bit
+            // pattern) redoes its word with the division.
+            const float r = 1.0f / s;
+            const bool fast = r > 0x1p-100f && r < 0x1p100f;
+            const float g = (p.qmaxf > 7.5f) ? 0x1p-14f : 0x1p-18f;
+            const float C = (0.5f - p.qminf) - g;
+            const float top = p.qmaxf - p.qminf;
+            u32 worst = fast ? 0u : 0x7F800000u;
+            int lv[PER];
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                const float u = fmaf(f[i], r, C);
+                const float z = __builtin_amdgcn_fractf(u);
+                worst = max(worst, __float_as_uint(z));
+                lv[i] = (int)__builtin_amdgcn_fmed3f(u - z, 0.0f, top) + (int)p.qminf;
+            }
+            if (worst > __float_as_uint(1.0f - 2.0f * g) - 1u) {
+#pragma unroll
+                for (int i = 0; i < PER; ++i) lv[i] = quantize_level(f[i], s, p.qminf, p.qmaxf);
+            }
+#pragma unroll
+            for (int i = 0; i < PER; ++i) word |= ((u32)lv[i] & ((1u << SB) - 1u)) << (SB * i);
         } else {
 #pragma unroll
             for (int i = 0; i < PER; ++i) {
