@@ -10,11 +10,12 @@
 //     ssq((x - mu) * gamma) * n  >  ssq((k - 1/2)*step - beta) * V,      ssq(v) = v * |v|,
 // V = M_n + n*eps the (stabilised) sum of squared deviations -- sigma never appears.  Elements
 // are independent here, so the workgroup's rows are re-read wave by wave with coalesced 16-byte
-// loads by all four waves, four elements per lane, four rows per batch, the next batch in flight.  The comparisons are monotone in k, so
+// loads by all four waves, four elements per lane, one row at a time, the next row in flight.  The comparisons are monotone in k, so
 // instead of all 2^b - 1 of them the kernel makes a guess with the hardware reciprocal square
-// root and then evaluates the comparator itself only at the guessed level and the one above,
-// stepping the guess until both agree; the guess only chooses which comparisons are made, every
-// decision is the comparator's.
+// root.  A guess that lies further from every half-integer than the proven distance between the
+// guess and the comparator's own boundary stands as it is; otherwise the comparator itself is
+// evaluated at the guessed level and the one above, stepping the guess until both agree, and
+// every decision is the comparator's.
 #include "layernorm.h"
 #include <type_traits>
 #include "vitq_dev.h"
@@ -28,6 +29,9 @@ namespace {
 // equals RN(d/k) for EVERY fp32 significand of d and every k <= 16384 -- checked exhaustively on
 // the CPU (2^23 significands x 16384 divisors, no mismatch) -- and the exponent of d only scales
 // all three steps, as long as q0 stays a normal number and nothing overflows: 2^-100 <= |d| <= 2^120.
+#ifndef VITQ_LN_RB
+#define VITQ_LN_RB 1      // rows a wave decides per batch in phase 2 (more cost registers, hence resident waves)
+#endif
 #ifndef VITQ_LN_CH
 #define VITQ_LN_CH 16      // elements a lane requests at a time in phase 1
 #endif
@@ -40,6 +44,7 @@ struct RkTable {
 };
 __device__ const RkTable g_rk{};
 
+constexpr float kLnGuard = 0x1p-21f;   // unit of the guard that lets a guessed level stand without the comparator
 constexpr int kLnRows = 64;       // rows per workgroup (one lane each in phase 1)
 constexpr int kLnThreads = 256;   // threads per workgroup: all four waves work in phase 2
 constexpr int kLnWaves = kLnThreads / 64;
@@ -136,21 +141,23 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_quantize_kernel(LnParams
     // ---- phase 2: levels, one row per wave at a time, four consecutive elements per lane ----
     const int lane = tid & 63, wave = tid >> 6;
     const float rstep = __builtin_amdgcn_rcpf(p.step);   // for the guess only
+    const bool step_ok = p.step >= 0x1p-20f && p.step <= 0x1p10f;
     const float qminf = (float)p.qmin, qmaxf = (float)p.qmax;
     const int span = p.qmax - p.qmin;
     const int padded = p.row_bytes16 * 8 / SB;           // columns of the 16-byte padded row
     for (int c0 = 4 * lane; c0 < padded; c0 += 256) {
         // this lane's four columns are the same for every row
-        float gm[4], bt[4];
+        float gm[4], bt[4], cg[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const bool ok = c0 + i < cols;
             gm[i] = ok ? p.gamma[c0 + i] : 0.0f;
             bt[i] = ok ? p.beta[c0 + i] : 0.0f;
+            cg[i] = fmaf(fabsf(bt[i] * rstep), 3.0f * kLnGuard, 3.0f * kLnGuard);   // the guess's guard, constant part
         }
         // Rows are taken in batches of RB; the loads of the next batch are in flight while the
         // current one is decided (the rows no longer sit in a near cache after phase 1).
-        constexpr int RB = 4, NB = kLnRows / kLnWaves / RB;
+        constexpr int RB = VITQ_LN_RB, NB = kLnRows / kLnWaves / RB;
         auto load_batch = [&](int bi, float (&v)[RB][4]) {
 #pragma unroll
             for (int k = 0; k < RB; ++k) {
@@ -186,20 +193,49 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_quantize_kernel(LnParams
         for (int bi = 0; bi < NB; ++bi) {
             if (row0 + wave + kLnWaves * (bi * RB) >= p.rows) break;      // no rows left for this wave
             if (bi + 1 < NB) load_batch(bi + 1, nxt);
+            // The guess.  In exact arithmetic on the fp32 values g, beta, step, V the comparator asks whether
+            // t* = (g / sigma + beta) / step exceeds lv - 1/2 (sigma^2 = V/n).  The value tp computed here with
+            // the hardware rsq / rcp differs from t* by at most (|g/(sigma*step)| + |beta/step|) * 2^-21, and
+            // the comparator's own fp32 evaluation moves its boundary by at most (2|lv| + |beta/step| + 1) *
+            // 2^-22 (five roundings on the two sides, two of them doubled by the squares).  So when tp is
+            // further than kLnGuard * (4|tp| + 3|beta/step| + 3) from every half-integer, rint(tp) is the level
+            // the comparator would count, and the comparator is not run; a NaN or an infinity makes the
+            // figure NaN, which compares above the limit as a bit pattern.  The relative-error model behind
+            // these bounds needs the squares to stay ordinary numbers: the guess is trusted only for
+            // 2^-20 <= step <= 2^10 and 2^-40 <= V <= 2^30 (then an underflowing g*|g| can differ from the
+            // exact product by 2^-139 at most, against |L - R| >= V * step^2 * d^2 for a value d levels from a
+            // boundary, and nothing overflows below the |tp| that the guard itself rejects).
             float L[RB][4], c[RB][4], V[RB];
+            u32 worst = step_ok ? 0u : 0x7FC00000u;
 #pragma unroll
             for (int k = 0; k < RB; ++k) {
                 const int r = wave + kLnWaves * (bi * RB + k);
                 const float mu = s_mu[r], rs = s_rs[r];
                 V[k] = s_v[r];
+                if (!(V[k] >= 0x1p-40f && V[k] <= 0x1p30f)) worst = 0x7FC00000u;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const float a = cur[k][i] - mu;
                     const float g = a * gm[i];
-                    const float gs = g * fabsf(g);
-                    L[k][i] = gs * nf;
-                    const float t = rintf(fmaf(g, rs, bt[i]) * rstep);
+                    const float tp = fmaf(g, rs, bt[i]) * rstep;
+                    const float t = rintf(tp);
+                    const float fig = fmaf(fabsf(tp), 4.0f * kLnGuard, fabsf(tp - t)) + cg[i];
+                    worst = max(worst, __float_as_uint(fig));
                     c[k][i] = (t == t) ? __builtin_amdgcn_fmed3f(t, qminf, qmaxf) : qminf;
+                }
+            }
+            const bool verify = __builtin_amdgcn_ballot_w64(worst > __float_as_uint(0.5f)) != 0;
+            if (verify) {
+#pragma unroll
+                for (int k = 0; k < RB; ++k) {
+                    const float mu = s_mu[wave + kLnWaves * (bi * RB + k)];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float a = cur[k][i] - mu;
+                        const float g = a * gm[i];
+                        const float gs = g * fabsf(g);
+                        L[k][i] = gs * nf;
+                    }
                 }
             }
             // comparator of Fig. 5(b): element (k, i) against the reference (lv - 1/2)*step
@@ -212,7 +248,7 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_quantize_kernel(LnParams
             };
             // level = qmin + #{lv : above(lv)}; above() is monotone in lv, so c is the level iff
             // above(c) (or c == qmin) and not above(c + 1) (or c == qmax)
-            for (int it = 0; it <= span; ++it) {
+            for (int it = 0; verify && it <= span; ++it) {
                 bool moved = false;
 #pragma unroll
                 for (int k = 0; k < RB; ++k)

@@ -136,3 +136,33 @@ def test_every_binary_exponent_of_the_input_scale():
     beta = rng.normal(0, 0.3, cols).astype(np.float32)
     for eps in (0.0, 1e-6):
         _check(x, gamma, beta, eps, np.float32(0.4), 4)
+
+
+@pytest.mark.parametrize("bits,gsign", [(4, 1.0), (4, -1.0), (8, 1.0), (3, 1.0)])
+def test_values_planted_on_both_sides_of_every_guard_band(bits, gsign):
+    """A guessed level stands without the comparator when it is provably far from a boundary.  beta is chosen
+    per column so that one element of that column sits a chosen distance (2^-27 .. 2^-12 levels, either
+    side) from a comparator boundary; every level must still be the oracle's."""
+    rows, cols, eps = 64, 768, np.float32(1e-6)
+    rng = np.random.default_rng(900 + bits)
+    x, gamma, _ = _case(rng, rows, cols)
+    gamma = (gamma * gsign).astype(np.float32)
+    lo, hi = vqo.qrange(bits)
+    step = np.float32(4.0 / hi)
+    # Eq. 5 in fp32, element order, all rows at once (the statistics do not depend on beta)
+    mu = np.zeros(rows, np.float32)
+    m2 = np.zeros(rows, np.float32)
+    for i in range(cols):
+        d1 = x[:, i] - mu
+        mu = mu + d1 / np.float32(i + 1)
+        m2 = m2 + d1 * (x[:, i] - mu)
+    V = (m2 + np.float32(cols) * eps).astype(np.float64)
+    sigma = np.sqrt(V / cols)
+    beta = np.zeros(cols, np.float32)
+    for j in range(cols):
+        r = j % rows
+        g = np.float32(np.float32(x[r, j] - mu[r]) * gamma[j])
+        k = int(rng.integers(lo + 1, hi + 1))
+        delta = float(rng.choice([-1.0, 1.0])) * 2.0 ** float(rng.uniform(-27, -12))
+        beta[j] = np.float32(float(step) * (k - 0.5 + delta) - float(g) / sigma[r])
+    _check(x, gamma, beta, eps, step, bits)
