@@ -384,10 +384,12 @@ __device__ __forceinline__ void epilogue_quant(const GemmParams &p, const v16i &
 // One v_permlane32_swap per register pair trades those halves, after which lane (l, g) owns all
 // 64 channels of ONE token (block g) and can walk them in order, as Eq. 5 requires: the mean and
 // the sum of squared deviations are the fp32 recurrences in element order, and every level is
-// decided by the sigma-free comparator (a guess from the hardware reciprocal square root only
-// picks which two comparisons are evaluated).  The fp32 linear output never leaves registers.
+// the sigma-free comparator's: a guess from the hardware reciprocal square root stands when it is
+// provably far from every boundary, and otherwise picks which two comparisons are evaluated.
+// The fp32 linear output never leaves registers.
 // gamma / beta / the folded scales are wave-uniform: staged in LDS once per tile and read as
 // broadcasts.
+constexpr float kHnGuard = 0x1p-21f;   // unit of the guard that lets a guessed level stand (see the LayerNorm kernel)
 template <int SB, int NTK, int PAIR>   // PAIR: token blocks 2*PAIR and 2*PAIR + 1 of the wave's NTK
 __device__ __forceinline__ void epilogue_headnorm(const GemmParams &p, v16i (&acc)[2][NTK], int shift, uint8_t *dst,
                                                   const float *scs64, const float *bs64, float step,
@@ -421,6 +423,7 @@ __device__ __forceinline__ void epilogue_headnorm(const GemmParams &p, v16i (&ac
     const float V = m2 + ne;
     const float rs = __builtin_amdgcn_rsqf(V / nf);          // for the guess only
     const float rstep = __builtin_amdgcn_rcpf(step);         // for the guess only
+    const bool stats_ok = step >= 0x1p-20f && step <= 0x1p10f && V >= 0x1p-40f && V <= 0x1p30f;
     const float qminf = p.qminf, qmaxf = p.qmaxf;
     const int span = (int)(qmaxf - qminf);
     const float bias8 = -qminf;
@@ -438,13 +441,23 @@ __device__ __forceinline__ void epilogue_headnorm(const GemmParams &p, v16i (&ac
             const float R = cs * V;
             return L > R;
         };
-        const float tt = rintf(fmaf(g, rs, bt) * rstep);
+        // The guess tp is within (|g/(sigma*step)| + |beta/step|) * 2^-21 of the exact-arithmetic value the
+        // comparator tests, and the comparator's own fp32 evaluation moves a boundary by at most
+        // (2|level| + |beta/step| + 1) * 2^-22: a guess further than 2^-21 * (4|tp| + 3|beta/step| + 3) from every
+        // half-integer is the level the comparator would count, and it is not run (stats_ok: the squares stay
+        // ordinary numbers, which that error model needs).  A NaN figure fails the test and is verified.
+        const float tp = fmaf(g, rs, bt) * rstep;
+        const float tt = rintf(tp);
         float c = (tt == tt) ? __builtin_amdgcn_fmed3f(tt, qminf, qmaxf) : qminf;
-        for (int it = 0; it <= span; ++it) {
-            const bool low_ok = (c <= qminf) || above(c);
-            const bool high_ok = (c >= qmaxf) || !above(c + 1.0f);
-            if (low_ok && high_ok) break;
-            c = c + (!low_ok ? -1.0f : 1.0f);
+        const float cgi = fmaf(fabsf(bt * rstep), 3.0f * kHnGuard, 3.0f * kHnGuard);
+        const float fig = fmaf(fabsf(tp), 4.0f * kHnGuard, fabsf(tp - tt)) + cgi;
+        if (!(stats_ok && fig <= 0.5f)) {
+            for (int it = 0; it <= span; ++it) {
+                const bool low_ok = (c <= qminf) || above(c);
+                const bool high_ok = (c >= qmaxf) || !above(c + 1.0f);
+                if (low_ok && high_ok) break;
+                c = c + (!low_ok ? -1.0f : 1.0f);
+            }
         }
         v[i] = c + bias8;                                  // stored biased: 0 .. qmax - qmin
         if ((i & 3) == 3) __builtin_amdgcn_sched_barrier(0);

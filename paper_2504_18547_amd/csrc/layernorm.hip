@@ -330,6 +330,7 @@ __global__ __launch_bounds__(256) void qkv_headnorm_kernel(HeadNormParams p) {
         const float step = which == 0 ? p.s_q : p.s_k;
         const float rs = __builtin_amdgcn_rsqf(V / nf);          // for the guess only
         const float rstep = __builtin_amdgcn_rcpf(step);         // for the guess only
+        const bool stats_ok = step >= 0x1p-20f && step <= 0x1p10f && V >= 0x1p-40f && V <= 0x1p30f;
         const int span = p.qmax - p.qmin;
         const float *gp = p.gamma + which * p.D + h * 64, *bp = p.beta + which * p.D + h * 64;
 #pragma unroll
@@ -350,13 +351,19 @@ __global__ __launch_bounds__(256) void qkv_headnorm_kernel(HeadNormParams p) {
                     const float R = cs * V;
                     return L > R;
                 };
-                const float tt = rintf(fmaf(g, rs, bt[i]) * rstep);
+                // (the guess stands when it is provably far from every boundary: see the kernel above)
+                const float tp = fmaf(g, rs, bt[i]) * rstep;
+                const float tt = rintf(tp);
                 float c = (tt == tt) ? __builtin_amdgcn_fmed3f(tt, qminf, qmaxf) : qminf;
-                for (int it = 0; it <= span; ++it) {
-                    const bool low_ok = (c <= qminf) || above(c);
-                    const bool high_ok = (c >= qmaxf) || !above(c + 1.0f);
-                    if (low_ok && high_ok) break;
-                    c = c + (!low_ok ? -1.0f : 1.0f);
+                const float cgi = fmaf(fabsf(bt[i] * rstep), 3.0f * kLnGuard, 3.0f * kLnGuard);
+                const float fig = fmaf(fabsf(tp), 4.0f * kLnGuard, fabsf(tp - tt)) + cgi;
+                if (!(stats_ok && fig <= 0.5f)) {
+                    for (int it = 0; it <= span; ++it) {
+                        const bool low_ok = (c <= qminf) || above(c);
+                        const bool high_ok = (c >= qmaxf) || !above(c + 1.0f);
+                        if (low_ok && high_ok) break;
+                        c = c + (!low_ok ? -1.0f : 1.0f);
+                    }
                 }
                 lv[4 * q + i] = c;
             }

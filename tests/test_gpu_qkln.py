@@ -129,3 +129,86 @@ def test_preln_block_with_qk_layernorm():
     h = vqo.linear(l2["q"], st["s_x2"], wts["w_fc1"], wts["sw_fc1"], bias=wts["b_fc1"], act=1, s_y=st["s_h"], bits_y=4)["yq"]
     t = vqo.linear(h, st["s_h"], wts["w_fc2"], wts["sw_fc2"], bias=wts["b_fc2"])["y"]
     assert np.array_equal(y.cpu().numpy(), t + l2["sum"])
+
+
+def _planted_beta(y, gamma, beta, eps, steps, bits, rng):
+    """beta (Q and K channels) moved so that, for channel j, the element of token j % M sits a chosen
+    distance (2^-27 .. 2^-12 levels, either side) from a comparator boundary of its (token, head) group."""
+    M = y.shape[0]
+    D = gamma.size // 2
+    lo, hi = vqo.qrange(bits)
+    beta = beta.copy()
+    for j in range(2 * D):
+        r = j % M
+        grp = y[r, (j // 64) * 64:(j // 64) * 64 + 64]
+        mu, m2 = np.float32(0), np.float32(0)
+        for i in range(64):                                  # Eq. 5 in fp32, element order
+            d1 = np.float32(grp[i] - mu)
+            mu = np.float32(mu + np.float32(d1 / np.float32(i + 1)))
+            m2 = np.float32(m2 + np.float32(d1 * np.float32(grp[i] - mu)))
+        sigma = np.sqrt(float(np.float32(m2 + np.float32(64.0) * eps)) / 64.0)
+        g = np.float32(np.float32(y[r, j] - mu) * gamma[j])
+        step = float(steps[j // D])
+        k = int(rng.integers(lo + 1, hi + 1))
+        delta = float(rng.choice([-1.0, 1.0])) * 2.0 ** float(rng.uniform(-27, -12))
+        beta[j] = np.float32(step * (k - 0.5 + delta) - float(g) / sigma)
+    return beta
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_headnorm_op_values_planted_on_both_sides_of_the_guard(bits):
+    rng = np.random.default_rng(4400 + bits)
+    B, H, N = 1, 2, 96
+    D, M = 64 * H, B * N
+    y = (rng.standard_normal((M, 3 * D)) * rng.uniform(0.3, 3, (M, 1)) + rng.uniform(-1, 1, (M, 1))).astype(np.float32)
+    ln = _ln(D)
+    ln["gamma"][::7] *= -1
+    lo, hi = vqo.qrange(bits)
+    s_q, s_k, s_v = np.float32(3.0 / hi), np.float32(2.5 / hi), np.float32(4.0 / hi)
+    ln["beta"] = _planted_beta(y, ln["gamma"], ln["beta"], ln["eps"], (s_q, s_k), bits, rng)
+    sa = storage_of(bits)
+    out = torch.full((3 * B * H * N, 64 * sa // 8), 0xFF, dtype=torch.uint8, device="cuda")
+    vitq.vq_qkv_headnorm(dev(y), B, H, N, dev(ln["gamma"]), dev(ln["beta"]), ln["eps"], s_q, s_k, s_v, bits, sa, out)
+    torch.cuda.synchronize()
+    got = vqo.unpack(out.cpu().numpy(), 64, sa).reshape(3, B, H, N, 64)
+    for which, step in ((0, s_q), (1, s_k)):
+        for h in range(H):
+            sl = slice(which * D + h * 64, which * D + (h + 1) * 64)
+            ref = vqo.layernorm_quantize(y[:, sl], ln["gamma"][sl], ln["beta"][sl], ln["eps"], step, bits)["q"]
+            assert np.array_equal(got[which][:, h].reshape(M, 64), ref), (which, h)
+
+
+def test_fused_epilogue_values_planted_on_both_sides_of_the_guard():
+    """The same through the QKV linear's epilogue: with zero QKV weights the linear's output is its bias
+    (every token alike), so beta can be placed against the statistics of the bias."""
+    name, bits = "tiny_attn", 4
+    dims = wl.block_dims(name)
+    D, H, N = dims["D"], dims["H"], dims["N"]
+    B = 2
+    lo, hi = vqo.qrange(bits)
+    st = dict(wl.block_steps(name, True, bits, bits))
+    st["s_q"] = st["s_k"] = np.float32(3.0 / hi)
+    wts = quantized_weights(wl.block_weights(name, sharp=True), bits)
+    rng = np.random.default_rng(77)
+    wts["w_qkv"] = np.zeros_like(wts["w_qkv"])
+    wts["b_qkv"] = (rng.standard_normal(3 * D) * 1.5 + 0.3).astype(np.float32)
+    ybias = np.tile(wts["b_qkv"], (B * N, 1)).astype(np.float32)
+    ln = _ln(D)
+    ln["beta"] = _planted_beta(ybias, ln["gamma"], ln["beta"], ln["eps"], (st["s_q"], st["s_k"]), bits, rng)
+    wd = device_weights(wts, bits)
+    tokens = wl.block_tokens(name, list(range(B))).reshape(B * N, D)
+    xq_ref = vqo.quantize(tokens, st["s_x"], bits)
+    xq = vitq.QMat.empty(B * N, D, bits)
+    vitq.vq_quantize(dev(tokens), st["s_x"], None, xq)
+    dump = {"qkv": torch.zeros((3 * B * H * N, 64 * 4 // 8), dtype=torch.uint8, device="cuda")}
+    lnd = dict(gamma=dev(ln["gamma"]), beta=dev(ln["beta"]), eps=ln["eps"])
+    desc = vitq.make_block_desc(dims, bits, bits, 4, wd, st, dump, qkln=lnd)
+    ws = torch.empty(vitq.vq_attention_block_workspace(desc, B), dtype=torch.uint8, device="cuda")
+    y = torch.empty((B * N, D), dtype=torch.float32, device="cuda")
+    vitq.vq_attention_block(desc, xq, B, y, ws)
+    torch.cuda.synchronize()
+    ref = vqo.attention_block(xq_ref, B, dims, wts, st, bits_a=bits, bits_p=bits, qkln=ln)
+    qkv = vqo.unpack(dump["qkv"].cpu().numpy(), 64, 4).reshape(3, B, H, N, 64)
+    for i, nm in enumerate("qkv"):
+        assert np.array_equal(qkv[i], ref[nm]), "%s levels differ (%d)" % (nm, (qkv[i] != ref[nm]).sum())
+    assert np.array_equal(y.cpu().numpy(), ref["y"])
